@@ -1,0 +1,152 @@
+/*
+ * heart.h -- C ABI of the MI355X (gfx950) implementation of the data-parallel hot
+ * path of HEART's sparse-attention step for video diffusion transformers.
+ *
+ * One denoising step of one attention layer calls, in this order (the paper's
+ * Temporal Mask Reuse procedure, Alg. 1):
+ *     heart_pool_qk  ->  heart_drift  ->  heart_mask_topp  ->  heart_block_sparse_attn
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller (for instance the
+ *     storage of PyTorch-ROCm tensors).  The library allocates nothing, keeps no
+ *     state between calls, reads no environment variable.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call
+ *     only enqueues kernels on that stream and returns; it never synchronises.
+ *   - Return value: HEART_OK (0) or a negative error code.  After an error
+ *     heart_last_error() returns a thread-local message.  Arguments are validated on
+ *     the host before anything is launched; a call that fails launches nothing.
+ *   - Notation: B batch items (a classifier-free-guidance branch is its own batch
+ *     item), H heads, N tokens, D head dimension, `block` tokens per block,
+ *     Nb = ceil(N / block); the last block may hold fewer than `block` tokens.
+ *   - bf16 tensors are passed as const void* to 2-byte brain-float elements.
+ *   - NaN/Inf in inputs is undefined behaviour of the arithmetic (never of memory).
+ */
+#ifndef HEART_H_
+#define HEART_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HEART_OK 0
+#define HEART_EINVAL (-1)       /* null pointer, non-positive size, bad flag */
+#define HEART_EUNSUPPORTED (-2) /* shape outside what the kernels are built for */
+#define HEART_EHIP (-3)         /* the HIP runtime refused a launch */
+
+#define HEART_MAX_NB 1024 /* largest number of blocks per sequence the mask kernel ranks */
+
+/*
+ * Shape and memory layout of the Q/K/V/O tensors of one call.
+ * Logical shape is [B, H, N, D] with the D axis contiguous (stride 1).  The other
+ * three strides are given in ELEMENTS as {batch, head, token}, so both a
+ * [B,H,N,D] and a [B,N,H,D] allocation can be passed without a copy.
+ * Every base pointer and every stride (in bytes) must be a multiple of 16.
+ * Supported: D in {64, 128}; block in {64, 128}.
+ */
+typedef struct heart_shape {
+  int B, H, N, D, block;
+  long long q_stride[3];
+  long long k_stride[3];
+  long long v_stride[3];
+  long long o_stride[3];
+} heart_shape;
+
+/*
+ * Pooling (Alg. 1, step 1; Eq. 4; block granularity of the importance ranking,
+ * Sec. 4.2 and the appendix on baseline configurations).
+ * One streaming pass over bf16 Q and K yields
+ *   qblk, kblk   [B,H,Nb,D] fp32: mean over the real tokens of each block
+ *   qmean, kmean [B,H,D]    fp32: mean over all N tokens (token-averaged features
+ *                                 of Eq. 4; sum of block sums / N, which differs
+ *                                 from the mean of block means when the last
+ *                                 block is short)
+ * Outputs are contiguous.  Accumulation is fp32 inside a block in a fixed order
+ * (results are reproducible run to run) and fp64 across blocks.
+ * v_stride / o_stride of `shape` are ignored.
+ */
+int heart_pool_qk(const heart_shape *shape, const void *q_bf16, const void *k_bf16, float *qblk,
+                  float *kblk, float *qmean, float *kmean, void *stream);
+
+/*
+ * Mean-pooled drift, reuse rule and layer-level gate (Eq. 4; Sec. 4.2; Alg. 1;
+ * gate thresholds in the appendix on HEART configurations).
+ *   drift[b,h]   = sum_d |qanchor - qmean| + |kanchor - kmean|   (fp32, fixed halving
+ *                  tree over d, so the value is a pure function of the inputs;
+ *                  +inf for a head without an anchor)
+ *   mark[b,h]    = !has_anchor  ||  drift > delta[h]             (strict, Alg. 1)
+ *   gate, per batch item: frac = (#marks)/H in fp32;
+ *                  frac < gate_lo : heads that have an anchor reuse, others refresh
+ *                  frac > gate_hi : every head refreshes
+ *                  otherwise      : refresh = mark
+ *                  (gate_lo = 0, gate_hi = 1 disables the gate)
+ *   commit != 0  : for refreshed heads qanchor/kanchor <- qmean/kmean and
+ *                  has_anchor <- 1; reused heads keep their anchor (Alg. 1).
+ * qmean, kmean, qanchor, kanchor: fp32 [B,H,D] contiguous; has_anchor, refresh:
+ * uint8 [B,H]; delta: fp32 [H] (device); drift: fp32 [B,H].
+ * D must be a power of two, 1 <= D <= 512; H <= 4096.
+ */
+int heart_drift(int B, int H, int D, const float *qmean, const float *kmean, float *qanchor,
+                float *kanchor, unsigned char *has_anchor, const float *delta, float gate_lo,
+                float gate_hi, int commit, float *drift, unsigned char *refresh, void *stream);
+
+/*
+ * Block importance and top-p block mask for refreshed heads (top-p rule of
+ * Sec. 3.2; minimal set reaching the mass, Eq. 1; scale 1/sqrt(D) of the
+ * query-key interaction in the appendix; p = 1 is the dense value).
+ *   scores P[i,j] = softmax_j( qblk_i . kblk_j / sqrt(D) )       (dot products fp64,
+ *                   exponentials fp32)
+ *   per row i: rank key blocks by P descending, equal scores by lower index; with
+ *   u_j = floor(P_j * 2^30) and T = floor(tau_h * 2^24) keep the shortest prefix
+ *   whose  sum(u) * 2^24 >= T * (row total of u);  at least max(1, min_keep)
+ *   blocks; tau_h >= 1 keeps all.  The integer mass makes the kept set independent
+ *   of summation order.  Then key-block columns j < n_always_kv_blocks are kept in
+ *   every row and query rows i < n_dense_q_blocks keep every column.
+ * Inputs : qblk, kblk fp32 [B,H,Nb,D] (may both be NULL if scores_in is given);
+ *          scores_in fp32 [B,H,Nb,Nb] or NULL: if given, the score stage is skipped
+ *          and these scores are ranked instead (each must lie in [0,1]);
+ *          tau fp32 [H] (device), each > 0; refresh uint8 [B,H] or NULL (= all heads).
+ * Outputs, written only for heads with refresh != 0 (cached masks of reused heads
+ * persist, Alg. 1):
+ *          mask uint8 [B,H,Nb,Nb] (1 = kept);
+ *          kept_idx int32 [B,H,Nb,Nb]: ascending kept key-block indices of each
+ *            row in its first kept_count entries (the rest is left untouched);
+ *          kept_count int32 [B,H,Nb];
+ *          scores_out fp32 [B,H,Nb,Nb] or NULL.
+ * Supported: Nb <= HEART_MAX_NB; D a multiple of 4, D <= 256.
+ */
+int heart_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float *kblk,
+                    const float *scores_in, const float *tau, const unsigned char *refresh,
+                    int n_always_kv_blocks, int n_dense_q_blocks, int min_keep,
+                    unsigned char *mask, int *kept_idx, int *kept_count, float *scores_out,
+                    void *stream);
+
+/*
+ * Block-sparse attention consuming the mask as per-row kept-block lists
+ * (the sparse attention the mask is produced for; interaction scale from the
+ * appendix on query-key stability).
+ *   For head (b,h) and query block i:
+ *     out[n,:] = sum_t softmax_t( q_n . k_t * scale ) v_t,   t over the real tokens of
+ *     the key blocks kept_idx[b,h,i,0..kept_count[b,h,i])
+ *   computed flash-style (online softmax) with bf16 MFMA and fp32 accumulation.
+ * q, k, v: bf16 with the strides of `shape`; out: bf16 with o_stride; kept_idx /
+ * kept_count as written by heart_mask_topp (indices must lie in [0, Nb); order
+ * does not matter for the result up to rounding); scale <= 0 means 1/sqrt(D);
+ * lse: fp32 [B,H,N] natural-log-sum-exp of the scaled logits over the kept keys,
+ * or NULL.  A row with kept_count == 0 yields zeros (lse = -inf).
+ */
+int heart_block_sparse_attn(const heart_shape *shape, const void *q_bf16, const void *k_bf16,
+                            const void *v_bf16, const int *kept_idx, const int *kept_count,
+                            float scale, void *out_bf16, float *lse, void *stream);
+
+/* Thread-local message of the last error returned on this thread ("" if none). */
+const char *heart_last_error(void);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int heart_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HEART_H_ */

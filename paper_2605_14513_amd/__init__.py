@@ -1,0 +1,16 @@
+"""MI355X-native hot path of HEART's sparse-attention step (gfx950 HIP kernels
+behind a C ABI).  `binding` mirrors the four entry points of include/heart.h on
+torch-ROCm tensors; it only marshals arguments -- every step runs in the HIP
+kernels, and importing/calling it without the built library fails loudly."""
+from .binding import (  # noqa: F401
+    HeartError,
+    HeartShape,
+    heart_block_sparse_attn,
+    heart_drift,
+    heart_last_error,
+    heart_mask_topp,
+    heart_pool_qk,
+    heart_version,
+    lib_path,
+    load_library,
+)

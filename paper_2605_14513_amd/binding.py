@@ -1,0 +1,229 @@
+"""ctypes binding of libheart.so.  Argument marshalling only.
+
+Functions take torch tensors that live on the GPU, pass their device pointers,
+shapes and strides to the C ABI declared in include/heart.h, and enqueue on
+torch's current HIP stream.  There is no fallback: if the library is missing or
+a tensor is not on the GPU, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libheart.so")
+_lib: Optional[ctypes.CDLL] = None
+
+
+class HeartError(RuntimeError):
+    """A libheart entry point returned a negative code."""
+
+    def __init__(self, fn: str, code: int, msg: str):
+        super().__init__(f"{fn} failed with code {code}: {msg}")
+        self.code = code
+
+
+class HeartShape(ctypes.Structure):
+    """Mirror of `heart_shape` in include/heart.h."""
+
+    _fields_ = [
+        ("B", ctypes.c_int), ("H", ctypes.c_int), ("N", ctypes.c_int), ("D", ctypes.c_int),
+        ("block", ctypes.c_int),
+        ("q_stride", ctypes.c_longlong * 3), ("k_stride", ctypes.c_longlong * 3),
+        ("v_stride", ctypes.c_longlong * 3), ("o_stride", ctypes.c_longlong * 3),
+    ]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libheart.so (built by paper_2605_14513_amd.build); raise if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is not built; run `python -m paper_2605_14513_amd.build` "
+            "(there is no CPU or PyTorch fallback for the HEART kernels)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    sp = ctypes.POINTER(HeartShape)
+    lib.heart_pool_qk.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp]
+    lib.heart_drift.argtypes = [ci, ci, ci, vp, vp, vp, vp, vp, vp, cf, cf, ci, vp, vp, vp]
+    lib.heart_mask_topp.argtypes = [ci, ci, ci, ci, vp, vp, vp, vp, vp, ci, ci, ci, vp, vp, vp,
+                                    vp, vp]
+    lib.heart_block_sparse_attn.argtypes = [sp, vp, vp, vp, vp, vp, cf, vp, vp, vp]
+    for f in (lib.heart_pool_qk, lib.heart_drift, lib.heart_mask_topp,
+              lib.heart_block_sparse_attn, lib.heart_version):
+        f.restype = ci
+    lib.heart_last_error.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def heart_last_error() -> str:
+    return load_library().heart_last_error().decode()
+
+
+def heart_version() -> int:
+    return int(load_library().heart_version())
+
+
+def _check(fn: str, rc: int) -> None:
+    if rc != 0:
+        raise HeartError(fn, rc, heart_last_error())
+
+
+def _dev(t: Optional[torch.Tensor], dtype, name: str, contiguous: bool = True):
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or t.device.type != "cuda":
+        raise TypeError(f"{name} must be a GPU tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if contiguous and not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _strides_bhn(t: torch.Tensor, name: str) -> Tuple[int, int, int]:
+    if t.dim() != 4 or t.stride(3) != 1:
+        raise ValueError(f"{name} must be [B,H,N,D] with a contiguous D axis")
+    return t.stride(0), t.stride(1), t.stride(2)
+
+
+def make_shape(q: torch.Tensor, k: torch.Tensor, block: int, v: Optional[torch.Tensor] = None,
+               o: Optional[torch.Tensor] = None) -> HeartShape:
+    B, H, N, D = q.shape
+    s = HeartShape()
+    s.B, s.H, s.N, s.D, s.block = B, H, N, D, block
+    s.q_stride[:] = _strides_bhn(q, "q")
+    s.k_stride[:] = _strides_bhn(k, "k")
+    s.v_stride[:] = _strides_bhn(v if v is not None else k, "v")
+    s.o_stride[:] = _strides_bhn(o if o is not None else q, "out")
+    return s
+
+
+def heart_pool_qk(q: torch.Tensor, k: torch.Tensor, block: int, qblk=None, kblk=None, qmean=None,
+                  kmean=None):
+    """Block means [B,H,Nb,D] and token means [B,H,D] of bf16 q, k ([B,H,N,D] views)."""
+    lib = load_library()
+    if q.shape != k.shape:
+        raise ValueError("q and k must have the same shape")
+    B, H, N, D = q.shape
+    Nb = (N + block - 1) // block
+    f32 = dict(dtype=torch.float32, device=q.device)
+    qblk = torch.empty((B, H, Nb, D), **f32) if qblk is None else qblk
+    kblk = torch.empty((B, H, Nb, D), **f32) if kblk is None else kblk
+    qmean = torch.empty((B, H, D), **f32) if qmean is None else qmean
+    kmean = torch.empty((B, H, D), **f32) if kmean is None else kmean
+    shape = make_shape(q, k, block)
+    rc = lib.heart_pool_qk(ctypes.byref(shape), _dev(q, torch.bfloat16, "q", False),
+                           _dev(k, torch.bfloat16, "k", False), _dev(qblk, torch.float32, "qblk"),
+                           _dev(kblk, torch.float32, "kblk"), _dev(qmean, torch.float32, "qmean"),
+                           _dev(kmean, torch.float32, "kmean"), _stream())
+    _check("heart_pool_qk", rc)
+    return qblk, kblk, qmean, kmean
+
+
+def heart_drift(qmean, kmean, qanchor, kanchor, has_anchor, delta, gate_lo: float = 0.4,
+                gate_hi: float = 0.8, commit: bool = True, drift=None, refresh=None):
+    """Drift, reuse rule, layer gate; updates qanchor/kanchor/has_anchor in place."""
+    lib = load_library()
+    B, H, D = qmean.shape
+    drift = torch.empty((B, H), dtype=torch.float32, device=qmean.device) if drift is None else drift
+    refresh = torch.empty((B, H), dtype=torch.uint8, device=qmean.device) if refresh is None else refresh
+    if delta.numel() != H:
+        raise ValueError("delta must have H entries")
+    for t, n in ((kmean, "kmean"), (qanchor, "qanchor"), (kanchor, "kanchor")):
+        if tuple(t.shape) != (B, H, D):
+            raise ValueError(f"{n} must be [B,H,D]")
+    if tuple(has_anchor.shape) != (B, H) or tuple(drift.shape) != (B, H) or tuple(refresh.shape) != (B, H):
+        raise ValueError("has_anchor, drift, refresh must be [B,H]")
+    rc = lib.heart_drift(B, H, D, _dev(qmean, torch.float32, "qmean"),
+                         _dev(kmean, torch.float32, "kmean"),
+                         _dev(qanchor, torch.float32, "qanchor"),
+                         _dev(kanchor, torch.float32, "kanchor"),
+                         _dev(has_anchor, torch.uint8, "has_anchor"),
+                         _dev(delta, torch.float32, "delta"), float(gate_lo), float(gate_hi),
+                         1 if commit else 0, _dev(drift, torch.float32, "drift"),
+                         _dev(refresh, torch.uint8, "refresh"), _stream())
+    _check("heart_drift", rc)
+    return drift, refresh
+
+
+def heart_mask_topp(qblk, kblk, tau, refresh=None, scores_in=None, n_always_kv_blocks: int = 0,
+                    n_dense_q_blocks: int = 0, min_keep: int = 1, mask=None, kept_idx=None,
+                    kept_count=None, scores_out=None):
+    """Top-p block mask; writes mask/kept_idx/kept_count in place for refreshed heads."""
+    lib = load_library()
+    if scores_in is not None:
+        B, H, Nb, _ = scores_in.shape
+        D = 0 if qblk is None else qblk.shape[-1]
+        dev = scores_in.device
+    else:
+        B, H, Nb, D = qblk.shape
+        dev = qblk.device
+    if mask is None:
+        mask = torch.zeros((B, H, Nb, Nb), dtype=torch.uint8, device=dev)
+    if kept_idx is None:
+        kept_idx = torch.full((B, H, Nb, Nb), -1, dtype=torch.int32, device=dev)
+    if kept_count is None:
+        kept_count = torch.zeros((B, H, Nb), dtype=torch.int32, device=dev)
+    if tau.numel() != H:
+        raise ValueError("tau must have H entries")
+    for t, shp, n in ((mask, (B, H, Nb, Nb), "mask"), (kept_idx, (B, H, Nb, Nb), "kept_idx"),
+                      (kept_count, (B, H, Nb), "kept_count")):
+        if tuple(t.shape) != shp:
+            raise ValueError(f"{n} must have shape {shp}")
+    if scores_out is not None and tuple(scores_out.shape) != (B, H, Nb, Nb):
+        raise ValueError("scores_out must be [B,H,Nb,Nb]")
+    if refresh is not None and tuple(refresh.shape) != (B, H):
+        raise ValueError("refresh must be [B,H]")
+    if scores_in is None and tuple(kblk.shape) != (B, H, Nb, D):
+        raise ValueError("kblk must match qblk")
+    rc = lib.heart_mask_topp(B, H, Nb, D, _dev(qblk, torch.float32, "qblk"),
+                             _dev(kblk, torch.float32, "kblk"),
+                             _dev(scores_in, torch.float32, "scores_in"),
+                             _dev(tau, torch.float32, "tau"), _dev(refresh, torch.uint8, "refresh"),
+                             int(n_always_kv_blocks), int(n_dense_q_blocks), int(min_keep),
+                             _dev(mask, torch.uint8, "mask"), _dev(kept_idx, torch.int32, "kept_idx"),
+                             _dev(kept_count, torch.int32, "kept_count"),
+                             _dev(scores_out, torch.float32, "scores_out"), _stream())
+    _check("heart_mask_topp", rc)
+    return mask, kept_idx, kept_count
+
+
+def heart_block_sparse_attn(q, k, v, block: int, kept_idx, kept_count, scale: float = 0.0,
+                            out=None, lse=None):
+    """Block-sparse attention over the kept key blocks; returns bf16 out like q."""
+    lib = load_library()
+    if q.shape != k.shape or q.shape != v.shape:
+        raise ValueError("q, k, v must have the same shape")
+    B, H, N, D = q.shape
+    Nb = (N + block - 1) // block
+    if out is None:
+        out = torch.empty_like(q)
+    if tuple(kept_idx.shape) != (B, H, Nb, Nb) or tuple(kept_count.shape) != (B, H, Nb):
+        raise ValueError("kept_idx must be [B,H,Nb,Nb] and kept_count [B,H,Nb]")
+    if lse is not None and tuple(lse.shape) != (B, H, N):
+        raise ValueError("lse must be [B,H,N]")
+    shape = make_shape(q, k, block, v, out)
+    rc = lib.heart_block_sparse_attn(ctypes.byref(shape), _dev(q, torch.bfloat16, "q", False),
+                                     _dev(k, torch.bfloat16, "k", False),
+                                     _dev(v, torch.bfloat16, "v", False),
+                                     _dev(kept_idx, torch.int32, "kept_idx"),
+                                     _dev(kept_count, torch.int32, "kept_count"), float(scale),
+                                     _dev(out, torch.bfloat16, "out", False),
+                                     _dev(lse, torch.float32, "lse"), _stream())
+    _check("heart_block_sparse_attn", rc)
+    return out

@@ -1,0 +1,142 @@
+// C ABI of libheart: argument validation and dispatch to the kernel launchers.
+// Everything is checked on the host before a kernel is enqueued, so that a bad
+// call returns an error code instead of a memory fault on the device.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "heart_internal.h"
+
+namespace heart {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+void clear_error() { g_err[0] = '\0'; }
+
+int check_launch(const char *what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(HEART_EHIP, "%s: %s", what, hipGetErrorString(e));
+  return HEART_OK;
+}
+
+static int check_shape(const heart_shape *s, const char *fn) {
+  if (!s) return fail(HEART_EINVAL, "%s: shape is NULL", fn);
+  if (s->B <= 0 || s->H <= 0 || s->N <= 0)
+    return fail(HEART_EINVAL, "%s: B, H, N must be positive (got %d, %d, %d)", fn, s->B, s->H,
+                s->N);
+  if (s->D != 64 && s->D != 128)
+    return fail(HEART_EUNSUPPORTED, "%s: D must be 64 or 128 (got %d)", fn, s->D);
+  if (s->block != 64 && s->block != 128)
+    return fail(HEART_EUNSUPPORTED, "%s: block must be 64 or 128 (got %d)", fn, s->block);
+  long long nb = ((long long)s->N + s->block - 1) / s->block;
+  if ((long long)s->B * s->H * nb > 0x7fffffffLL)
+    return fail(HEART_EUNSUPPORTED, "%s: B*H*Nb exceeds the 1-D grid limit", fn);
+  return HEART_OK;
+}
+
+}  // namespace heart
+
+using namespace heart;
+
+extern "C" {
+
+const char *heart_last_error(void) { return g_err; }
+
+int heart_version(void) { return 100; }
+
+int heart_pool_qk(const heart_shape *shape, const void *q, const void *k, float *qblk,
+                  float *kblk, float *qmean, float *kmean, void *stream) {
+  clear_error();
+  if (int rc = check_shape(shape, "heart_pool_qk")) return rc;
+  if (!q || !k || !qblk || !kblk || !qmean || !kmean)
+    return fail(HEART_EINVAL, "heart_pool_qk: NULL pointer argument");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(qblk) || !aligned16(kblk) ||
+      !aligned16(qmean) || !aligned16(kmean))
+    return fail(HEART_EUNSUPPORTED, "heart_pool_qk: pointers must be 16-byte aligned");
+  if (!stride_ok(shape->q_stride) || !stride_ok(shape->k_stride))
+    return fail(HEART_EUNSUPPORTED,
+                "heart_pool_qk: strides must be multiples of 8 elements, token stride > 0");
+  return launch_pool(*shape, q, k, qblk, kblk, qmean, kmean, (hipStream_t)stream);
+}
+
+int heart_drift(int B, int H, int D, const float *qmean, const float *kmean, float *qanchor,
+                float *kanchor, unsigned char *has_anchor, const float *delta, float gate_lo,
+                float gate_hi, int commit, float *drift, unsigned char *refresh, void *stream) {
+  clear_error();
+  if (B <= 0 || H <= 0 || D <= 0)
+    return fail(HEART_EINVAL, "heart_drift: B, H, D must be positive (got %d, %d, %d)", B, H, D);
+  if ((D & (D - 1)) != 0 || D > 512)
+    return fail(HEART_EUNSUPPORTED, "heart_drift: D must be a power of two <= 512 (got %d)", D);
+  if (H > 4096) return fail(HEART_EUNSUPPORTED, "heart_drift: H must be <= 4096 (got %d)", H);
+  if (!qmean || !kmean || !qanchor || !kanchor || !has_anchor || !delta || !drift || !refresh)
+    return fail(HEART_EINVAL, "heart_drift: NULL pointer argument");
+  if (!(gate_lo <= gate_hi))
+    return fail(HEART_EINVAL, "heart_drift: need gate_lo <= gate_hi (got %g, %g)", gate_lo,
+                gate_hi);
+  return launch_drift(B, H, D, qmean, kmean, qanchor, kanchor, has_anchor, delta, gate_lo,
+                      gate_hi, commit, drift, refresh, (hipStream_t)stream);
+}
+
+int heart_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float *kblk,
+                    const float *scores_in, const float *tau, const unsigned char *refresh,
+                    int n_always_kv_blocks, int n_dense_q_blocks, int min_keep,
+                    unsigned char *mask, int *kept_idx, int *kept_count, float *scores_out,
+                    void *stream) {
+  clear_error();
+  if (B <= 0 || H <= 0 || Nb <= 0)
+    return fail(HEART_EINVAL, "heart_mask_topp: B, H, Nb must be positive (got %d, %d, %d)", B,
+                H, Nb);
+  if (Nb > HEART_MAX_NB)
+    return fail(HEART_EUNSUPPORTED, "heart_mask_topp: Nb = %d exceeds HEART_MAX_NB = %d", Nb,
+                HEART_MAX_NB);
+  if (!scores_in) {
+    if (!qblk || !kblk)
+      return fail(HEART_EINVAL, "heart_mask_topp: need qblk and kblk, or scores_in");
+    if (D <= 0 || D % 4 != 0 || D > 256)
+      return fail(HEART_EUNSUPPORTED,
+                  "heart_mask_topp: D must be a positive multiple of 4, <= 256 (got %d)", D);
+    if (!aligned16(qblk) || !aligned16(kblk))
+      return fail(HEART_EUNSUPPORTED, "heart_mask_topp: qblk/kblk must be 16-byte aligned");
+  }
+  if (!tau || !mask || !kept_idx || !kept_count)
+    return fail(HEART_EINVAL, "heart_mask_topp: NULL pointer argument");
+  if (n_always_kv_blocks < 0 || n_dense_q_blocks < 0 || min_keep < 0)
+    return fail(HEART_EINVAL, "heart_mask_topp: negative block-count argument");
+  if ((long long)B * H * Nb > 0x7fffffffLL)
+    return fail(HEART_EUNSUPPORTED, "heart_mask_topp: B*H*Nb exceeds the 1-D grid limit");
+  return launch_mask_topp(B, H, Nb, D, qblk, kblk, scores_in, tau, refresh, n_always_kv_blocks,
+                          n_dense_q_blocks, min_keep, mask, kept_idx, kept_count, scores_out,
+                          (hipStream_t)stream);
+}
+
+int heart_block_sparse_attn(const heart_shape *shape, const void *q, const void *k,
+                            const void *v, const int *kept_idx, const int *kept_count,
+                            float scale, void *out, float *lse, void *stream) {
+  clear_error();
+  if (int rc = check_shape(shape, "heart_block_sparse_attn")) return rc;
+  if (!q || !k || !v || !kept_idx || !kept_count || !out)
+    return fail(HEART_EINVAL, "heart_block_sparse_attn: NULL pointer argument");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
+    return fail(HEART_EUNSUPPORTED,
+                "heart_block_sparse_attn: q/k/v/out must be 16-byte aligned");
+  if (!stride_ok(shape->q_stride) || !stride_ok(shape->k_stride) ||
+      !stride_ok(shape->v_stride) || !stride_ok(shape->o_stride))
+    return fail(HEART_EUNSUPPORTED,
+                "heart_block_sparse_attn: strides must be multiples of 8 elements, token "
+                "stride > 0");
+  if (shape->block == 64 && shape->D != 64)
+    return fail(HEART_EUNSUPPORTED,
+                "heart_block_sparse_attn: supported (D, block) pairs are (128,128), (64,128), "
+                "(64,64)");
+  return launch_attn(*shape, q, k, v, kept_idx, kept_count, scale, out, lse,
+                     (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,100 @@
+"""CPU-side checks of the boundary: the library builds, loads and exports every
+symbol that include/heart.h declares, and host-side validation rejects bad calls
+before anything touches a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2605_14513_amd import build as hb
+    from paper_2605_14513_amd import binding
+
+    if hb.is_stale():
+        hb.build(force=True)
+    return binding.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "heart.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(heart_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_four_hot_path_calls():
+    syms = declared_symbols()
+    for s in ("heart_pool_qk", "heart_drift", "heart_mask_topp", "heart_block_sparse_attn",
+              "heart_last_error", "heart_version"):
+        assert s in syms
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for s in declared_symbols():
+        assert hasattr(lib, s), f"libheart.so does not export {s}"
+    assert lib.heart_version() >= 100
+
+
+def test_binding_names_match_header():
+    import paper_2605_14513_amd as pkg
+
+    for s in declared_symbols():
+        assert hasattr(pkg, s), f"python binding lacks {s}"
+
+
+def test_shape_struct_layout_matches_header():
+    from paper_2605_14513_amd.binding import HeartShape
+
+    # 5 ints (20 bytes, padded to 24) + 4 * 3 long long
+    assert ctypes.sizeof(HeartShape) == 24 + 4 * 3 * 8
+    assert HeartShape.q_stride.offset == 24 and HeartShape.o_stride.offset == 24 + 72
+
+
+def test_host_validation_rejects_bad_calls_without_a_gpu(lib):
+    from paper_2605_14513_amd.binding import HeartShape
+
+    assert lib.heart_pool_qk(None, None, None, None, None, None, None, None) == -1
+    assert b"shape is NULL" in lib.heart_last_error()
+    s = HeartShape()
+    s.B, s.H, s.N, s.D, s.block = 1, 2, 100, 96, 128
+    assert lib.heart_pool_qk(ctypes.byref(s), None, None, None, None, None, None, None) == -2
+    assert b"D must be 64 or 128" in lib.heart_last_error()
+    s.D = 128
+    assert lib.heart_pool_qk(ctypes.byref(s), None, None, None, None, None, None, None) == -1
+    s.block = 100
+    assert lib.heart_block_sparse_attn(ctypes.byref(s), None, None, None, None, None, 0.0, None,
+                                       None, None) == -2
+    assert lib.heart_drift(1, 2, 96, None, None, None, None, None, None, 0.4, 0.8, 1, None, None,
+                           None) == -2
+    assert lib.heart_drift(1, 2, 64, None, None, None, None, None, None, 0.4, 0.8, 1, None, None,
+                           None) == -1
+    assert lib.heart_mask_topp(1, 1, 2000, 128, None, None, None, None, None, 0, 0, 1, None, None,
+                               None, None, None) == -2
+    assert b"HEART_MAX_NB" in lib.heart_last_error()
+    assert lib.heart_mask_topp(1, 1, 8, 128, None, None, None, None, None, 0, 0, 1, None, None,
+                               None, None, None) == -1
+
+
+def test_binding_refuses_cpu_tensors(lib):
+    import torch
+
+    import paper_2605_14513_amd as pkg
+
+    q = torch.zeros((1, 1, 128, 128), dtype=torch.bfloat16)
+    with pytest.raises(TypeError):
+        pkg.heart_pool_qk(q, q, 128, qblk=torch.zeros(1, 1, 1, 128), kblk=torch.zeros(1, 1, 1, 128),
+                          qmean=torch.zeros(1, 1, 128), kmean=torch.zeros(1, 1, 128))
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2605_14513_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+                assert "heart_oracle" not in text, f
