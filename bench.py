@@ -1,0 +1,262 @@
+#!/usr/bin/env python3
+"""Benchmark of the HEART sparse-attention hot path on one MI355X.
+
+A "step" is one pass of the whole path -- heart_pool_qk -> heart_drift ->
+heart_mask_topp -> heart_block_sparse_attn -- over the bf16 Q/K/V of one simulated
+denoising step of the Wan2.1-14B-shaped 480P workload (B=1, H=40, D=128,
+N=32760 = 21x30x52, block 128), with the inputs already resident in HBM.  The
+10-step synthetic schedule is cycled; TMR state (anchors, cached masks) carries
+from step to step and is cleared when the schedule wraps.
+
+Prints ONE JSON line.  `value` is kept-block attention FLOPs per step divided by
+the time of the WHOLE step (all four kernels), in TFLOP/s; per-kernel times, the
+mask-refresh time (pool + drift + mask), the roofline of the dominant kernel and
+the CPU oracle's rate on a bounded sample are reported beside it.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X dense bf16
+PEAK_HBM_GBS = 8000.0           # MI355X HBM3E
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="wan14b_480p")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gate", default="0.4,0.8", help="layer gate lo,hi (0,1 disables)")
+    return ap.parse_args()
+
+
+def kept_flops(kept_idx, kept_count, N, block, D):
+    """4*D*sum over kept (i,j) of n_i*n_j, exactly, from the kept lists (torch, on GPU)."""
+    import torch
+
+    Nb = kept_count.shape[-1]
+    n = torch.full((Nb,), block, dtype=torch.float64, device=kept_count.device)
+    n[Nb - 1] = N - (Nb - 1) * block
+    ar = torch.arange(Nb, device=kept_count.device)
+    valid = ar[None, None, None, :] < kept_count[..., None]
+    nj = n[kept_idx.clamp(0, Nb - 1).long()] * valid
+    per_row = nj.sum(-1) * n[None, None, :]
+    return float(4.0 * D * per_row.sum().item())
+
+
+def cpu_baseline(name, tau_all, delta_all):
+    """Oracle timed on host cores on a bounded sample of the same workload."""
+    import numpy as np
+
+    import oracle
+    from heart_synth import HeartInputGenerator, as_u16, get_config
+
+    cfg = get_config(name)
+    heads = sorted(set(np.linspace(0, cfg.H - 1, num=min(8, cfg.H)).astype(int).tolist()))
+    g = HeartInputGenerator(cfg, heads=heads)
+    st = g.step(0)
+    q, k, v = as_u16(st.q), as_u16(st.k), as_u16(st.v)
+    nh = len(heads)
+    t0 = time.perf_counter()
+    qb, qm = oracle.pool(q, cfg.block)
+    kb, km = oracle.pool(k, cfg.block)
+    qa = np.zeros_like(qm); ka = np.zeros_like(km); has = np.zeros((cfg.B, nh), np.uint8)
+    oracle.drift(qm, km, qa, ka, has, delta_all[heads], 0.4, 0.8)
+    sc = oracle.scores(qb, kb)
+    nt = cfg.n_text_blocks
+    m, idx, cnt = oracle.topp(sc, tau_all[heads], n_always_kv=nt, n_dense_q=nt)
+    t_mask = time.perf_counter() - t0
+    # attention on a sample of query blocks per head, sized for roughly 10-20 s of CPU work
+    rng = np.random.default_rng(0)
+    nq = min(30, cfg.Nb)
+    qblocks = sorted(set([0, cfg.Nb - 1] + rng.choice(cfg.Nb, size=nq, replace=False).tolist()))
+    t0 = time.perf_counter()
+    oracle.attn(q, k, v, cfg.block, idx, cnt, qblocks=qblocks)
+    t_attn = time.perf_counter() - t0
+    n = np.full(cfg.Nb, cfg.block, np.float64)
+    n[-1] = cfg.N - (cfg.Nb - 1) * cfg.block
+    fl = 0.0
+    for b in range(cfg.B):
+        for h in range(nh):
+            for i in qblocks:
+                fl += 4.0 * cfg.D * n[i] * n[idx[b, h, i, :cnt[b, h, i]]].sum()
+    return {
+        "value": fl / t_attn / 1e12,
+        "unit": "TFLOP/s",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": (f"step 0 of {name}, heads {heads}: pool+drift+scores+top-p in full for these "
+                   f"heads, sparse attention on query blocks {qblocks} of each; value = kept-block "
+                   f"attention FLOPs / oracle attention time"),
+        "attn_seconds_on_sample": t_attn,
+        "mask_refresh_us_per_step_extrapolated": t_mask * 1e6 * cfg.H / nh,
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one MI355X per box; no collectives, no "
+              f"sharding). --gpus {args.gpus} is not supported; run with --gpus 1.",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2605_14513_amd as heart
+    from heart_synth import make_generator
+
+    if not os.path.exists(heart.lib_path()):
+        from paper_2605_14513_amd import build as hb
+
+        hb.build(force=True)
+    heart.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    gate_lo, gate_hi = (float(x) for x in args.gate.split(","))
+
+    t_setup = time.perf_counter()
+    g = make_generator(args.workload)
+    cfg = g.cfg
+    B, H, N, D, Nb, blk = cfg.B, cfg.H, cfg.N, cfg.D, cfg.Nb, cfg.block
+    nt = cfg.n_text_blocks
+    S = cfg.steps
+    steps_in = []
+    for s in range(S):
+        st = g.step(s)
+        steps_in.append((st.q.to(dev), st.k.to(dev), st.v.to(dev)))
+        print(f"[bench] generated step {s + 1}/{S}", file=sys.stderr, flush=True)
+    tau = torch.from_numpy(g.tau).to(dev)
+    delta = torch.from_numpy(g.delta).to(dev)
+    del st
+    print(f"[bench] inputs resident after {time.perf_counter() - t_setup:.1f} s", file=sys.stderr,
+          flush=True)
+
+    f32 = dict(dtype=torch.float32, device=dev)
+    qblk = torch.empty((B, H, Nb, D), **f32); kblk = torch.empty((B, H, Nb, D), **f32)
+    qmean = torch.empty((B, H, D), **f32); kmean = torch.empty((B, H, D), **f32)
+    qa = torch.zeros((B, H, D), **f32); ka = torch.zeros((B, H, D), **f32)
+    has = torch.zeros((B, H), dtype=torch.uint8, device=dev)
+    drift = torch.empty((B, H), **f32)
+    refresh = torch.empty((B, H), dtype=torch.uint8, device=dev)
+    mask = torch.zeros((B, H, Nb, Nb), dtype=torch.uint8, device=dev)
+    kidx = torch.zeros((B, H, Nb, Nb), dtype=torch.int32, device=dev)
+    kcnt = torch.zeros((B, H, Nb), dtype=torch.int32, device=dev)
+    out = torch.empty_like(steps_in[0][0])
+
+    def one_step(it, ev=None):
+        s = it % S
+        q, k, v = steps_in[s]
+        if s == 0:
+            has.zero_()  # schedule wraps: no cached anchors
+        if ev: ev[0].record()
+        heart.heart_pool_qk(q, k, blk, qblk, kblk, qmean, kmean)
+        if ev: ev[1].record()
+        heart.heart_drift(qmean, kmean, qa, ka, has, delta, gate_lo, gate_hi, True, drift, refresh)
+        if ev: ev[2].record()
+        heart.heart_mask_topp(qblk, kblk, tau, refresh=refresh, n_always_kv_blocks=nt,
+                              n_dense_q_blocks=nt, mask=mask, kept_idx=kidx, kept_count=kcnt)
+        if ev: ev[3].record()
+        heart.heart_block_sparse_attn(q, k, v, blk, kidx, kcnt, out=out)
+        if ev: ev[4].record()
+
+    K, W = args.steps, args.warmup
+    for it in range(W):
+        one_step(it)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps, HIP events on the launch stream around each call ----
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K)]
+    stats = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for it in range(K):
+        one_step(it, events[it])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    per = np.array([[events[i][j].elapsed_time(events[i][j + 1]) for j in range(4)]
+                    for i in range(K)])  # ms
+    pool_ms, drift_ms, mask_ms, attn_ms = per.mean(0)
+
+    # ---- untimed replay of the same K steps to count kept-block FLOPs and refresh ratio ----
+    has.zero_(); kcnt.zero_()
+    flops, dens, refr = [], [], []
+    for it in range(K):
+        one_step(it)
+        torch.cuda.synchronize()
+        flops.append(kept_flops(kidx, kcnt, N, blk, D))
+        dens.append(float(kcnt.sum().item()) / (B * H * Nb * Nb))
+        refr.append(float(refresh.float().mean().item()))
+    flops_per_step = float(np.mean(flops))
+    dense_flops = 4.0 * N * N * D * H * B
+
+    value = flops_per_step / (ms_per_step * 1e-3) / 1e12
+    attn_tflops = flops_per_step / (attn_ms * 1e-3) / 1e12
+    pool_bytes = 2 * B * H * N * D * 2 + 2 * B * H * (Nb + 1) * D * 4
+    refreshed = float(np.mean(refr))
+    mask_bytes = refreshed * B * H * (2 * Nb * D * 4 + Nb * Nb * (1 + 4))
+
+    result = {
+        "metric": "sparse-attn effective TFLOP/s + mask-refresh us/step, Wan-14B 480P shape, 1 GPU",
+        "value": value,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{cfg.name}: B={B} H={H} D={D} N={N} grid={'x'.join(map(str, cfg.grid))} "
+                        f"block={blk}, {S}-step synthetic TMR schedule, gate {gate_lo}/{gate_hi}",
+            "value_definition": "kept-block attention FLOPs (4*D*sum n_i*n_j over kept blocks) per "
+                                "step / wall time of the whole step (pool+drift+mask+attention)",
+        },
+        "mask_refresh_us_per_step": (pool_ms + drift_ms + mask_ms) * 1e3,
+        "kernels_us": {"pool_qk": pool_ms * 1e3, "drift": drift_ms * 1e3,
+                       "mask_topp": mask_ms * 1e3, "block_sparse_attn": attn_ms * 1e3},
+        "attn_kept_tflops": attn_tflops,
+        "attn_dense_equiv_tflops": dense_flops / (attn_ms * 1e-3) / 1e12,
+        "kept_block_density": float(np.mean(dens)),
+        "refreshed_head_fraction": refreshed,
+        "roofline": {
+            "kernel": "heart_block_sparse_attn",
+            "bound": "mfma",
+            "achieved": attn_tflops,
+            "peak": PEAK_BF16_MFMA_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": attn_tflops / PEAK_BF16_MFMA_TFLOPS,
+            "traffic": None,
+        },
+        "roofline_hbm_kernels": {
+            "heart_pool_qk": {"bound": "hbm", "achieved": pool_bytes / (pool_ms * 1e-3) / 1e9,
+                              "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                              "frac": pool_bytes / (pool_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
+            "heart_mask_topp": {"bound": "hbm", "achieved": mask_bytes / (mask_ms * 1e-3) / 1e9,
+                                "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                "frac": mask_bytes / (mask_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
+        },
+    }
+    if not args.no_cpu_baseline:
+        print("[bench] timing the CPU oracle on a bounded sample", file=sys.stderr, flush=True)
+        result["cpu_baseline"] = cpu_baseline(args.workload, g.tau, g.delta)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

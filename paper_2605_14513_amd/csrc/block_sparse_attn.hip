@@ -38,10 +38,15 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
+// Native vector types (not the HIP struct wrappers): loads and stores of these are
+// first-class values, so staging arrays of them always live in registers.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+
 union Frag8 {
-  uint4 u;
+  u32x4_t u;
   bf16x8_t v;
-  uint2 h[2];
+  u32x2_t h[2];
 };
 
 __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
@@ -50,10 +55,16 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, b);
 }
 
+// registers that carry one thread's share of a K or V tile from global memory to LDS
+template <int n>
+struct KStage {
+  u32x4_t r[n];
+};
+
 constexpr int kNumXcd = 8;
 
 template <int D, int BLK>
-__global__ __launch_bounds__(BLK * 2) void attn_kernel(
+__global__ __launch_bounds__(BLK * 2, 2) void attn_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k,
     const uint16_t *__restrict__ v, uint16_t *__restrict__ out, long long qsb, long long qsh,
     long long qsn, long long ksb, long long ksh, long long ksn, long long vsb, long long vsh,
@@ -67,6 +78,11 @@ __global__ __launch_bounds__(BLK * 2) void attn_kernel(
   constexpr int SK = D + 8;         // LDS row stride of the K tile (elements)
   constexpr int SV = BLK + 4;       // LDS row stride of the V^T tile (elements)
   constexpr int CPR = D / 8;        // 16-byte chunks per token row
+  constexpr int KCH = (BLK * CPR) / NT;  // K chunks per thread
+  constexpr int VIT = D / 64;            // V sub-tiles (4 keys x 8 d) per thread
+  constexpr int KTH = 2;                 // 32-key tiles per slice of the key block
+  constexpr int NH = KT / KTH;           // slices per key block
+  constexpr float kRescaleSlack = 8.f;   // log2 units the running reference may lag the max
 
   extern __shared__ __align__(16) unsigned char smem_raw[];
   uint16_t *sK = reinterpret_cast<uint16_t *>(smem_raw);  // [BLK][SK]; reused for the output
@@ -97,146 +113,234 @@ __global__ __launch_bounds__(BLK * 2) void attn_kernel(
   const uint16_t *kbase = k + b * ksb + h * ksh;
   const uint16_t *vbase = v + b * vsb + h * vsh;
 
+  // per-thread constant parts of the staging addresses: K chunk `it` of this thread is
+  // row k_r0 + it * (NT / CPR), column k_c; V sub-tile `it` is d-group v_dg, key-group
+  // v_kg0 + it * V_KG_STEP (see the file header for why this mapping is conflict free)
+  const int k_r0 = t / CPR, k_c = (t % CPR) * 8;
+  constexpr int K_R_STEP = NT / CPR;
+  const int v_dg = (t & 3) + 4 * ((t >> 5) % (D / 32));
+  const int v_kg0 = ((t & 31) >> 2) + 8 * ((t >> 5) / (D / 32));
+  constexpr int V_KG_STEP = 8 * ((NT / 32) / (D / 32));
+
+  // Rows past the end of a ragged last block are loaded from the block's last real row
+  // instead (always a valid address): their logits are masked to -inf and their
+  // softmax weights are exactly 0, so the values never reach the output.
+  auto load_k = [&](int kv0, int nvalid) -> KStage<KCH> {
+    KStage<KCH> st;
+#pragma unroll
+    for (int it = 0; it < KCH; ++it) {
+      const int r = min(k_r0 + it * K_R_STEP, nvalid - 1);
+      st.r[it] = *reinterpret_cast<const u32x4_t *>(kbase + (long long)(kv0 + r) * ksn + k_c);
+    }
+    return st;
+  };
+  auto store_k = [&](const KStage<KCH> &st) {
+    uint16_t *dst = sK + k_r0 * SK + k_c;
+#pragma unroll
+    for (int it = 0; it < KCH; ++it)
+      *reinterpret_cast<u32x4_t *>(dst + it * K_R_STEP * SK) = st.r[it];
+  };
+  // V staging is done per 64-key slice `half` of the key block.  With VIT == NH a
+  // thread's sub-tile `it` lies in slice `it`; with VIT == 1 its single sub-tile
+  // lies in slice v_kg0 / KGH (uniform per wavefront).
+  constexpr int KGH = 16;  // key groups (of 4 keys) per slice
+  static_assert(VIT == NH || VIT == 1, "V staging layout");
+  auto v_mine = [&](int it, int half) -> bool {
+    return VIT == NH ? it == half : (v_kg0 / KGH) == half;
+  };
+  auto load_v = [&](int half, int kv0, int nvalid) -> KStage<4> {
+    KStage<4> st;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) st.r[e] = u32x4_t{0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int it = 0; it < VIT; ++it)
+      if (v_mine(it, half)) {
+        const int kg = v_kg0 + it * V_KG_STEP;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = min(kg * 4 + e, nvalid - 1);
+          st.r[e] = *reinterpret_cast<const u32x4_t *>(vbase + (long long)(kv0 + r) * vsn + v_dg * 8);
+        }
+      }
+    return st;
+  };
+  auto store_vt = [&](const KStage<4> &vst, int half) {
+    const u32x4_t *vreg = vst.r;
+#pragma unroll
+    for (int it = 0; it < VIT; ++it)
+      if (v_mine(it, half)) {
+        const uint32_t w[4][4] = {{vreg[0].x, vreg[0].y, vreg[0].z, vreg[0].w},
+                                  {vreg[1].x, vreg[1].y, vreg[1].z, vreg[1].w},
+                                  {vreg[2].x, vreg[2].y, vreg[2].z, vreg[2].w},
+                                  {vreg[3].x, vreg[3].y, vreg[3].z, vreg[3].w}};
+        uint16_t *dst = sVT + (v_dg * 8) * SV + (v_kg0 + it * V_KG_STEP) * 4;
+#pragma unroll
+        for (int wd = 0; wd < 4; ++wd) {
+          // word wd of key e holds d = 2*wd (low half) and d = 2*wd+1 (high half)
+          u32x2_t even, odd;
+          even.x = __builtin_amdgcn_perm(w[1][wd], w[0][wd], 0x05040100u);  // lo16(k0) | lo16(k1)<<16
+          even.y = __builtin_amdgcn_perm(w[3][wd], w[2][wd], 0x05040100u);
+          odd.x = __builtin_amdgcn_perm(w[1][wd], w[0][wd], 0x07060302u);   // hi16(k0) | hi16(k1)<<16
+          odd.y = __builtin_amdgcn_perm(w[3][wd], w[2][wd], 0x07060302u);
+          *reinterpret_cast<u32x2_t *>(dst + (2 * wd) * SV) = even;
+          *reinterpret_cast<u32x2_t *>(dst + (2 * wd + 1) * SV) = odd;
+        }
+      }
+  };
+
   // ---- Q fragments (B operand of S^T = K Q^T), kept in registers ----------------
+  // (query rows past N read row N-1; their results are never stored)
   const int qrow = qb * BLK + wave * 32 + l32;
   Frag8 qf[KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    qf[ks].u = make_uint4(0u, 0u, 0u, 0u);
-    if (qrow < N)
-      qf[ks].u = *reinterpret_cast<const uint4 *>(qbase + (long long)qrow * qsn + ks * 16 + hf * 8);
-  }
+  for (int ks = 0; ks < KS; ++ks)
+    qf[ks].u = *reinterpret_cast<const u32x4_t *>(qbase + (long long)min(qrow, N - 1) * qsn +
+                                                ks * 16 + hf * 8);
 
   f32x16_t o[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
-  float m_run = -__builtin_inff();  // running max of the logits, log2 domain
-  float l_run = 0.f;                // running sum over this lane's keys
+  float m_ref = -__builtin_inff();  // reference exponent (log2 domain) of the running sums
+  float l_run = 0.f;                // running sum over this lane's keys, relative to m_ref
 
   const size_t row = (size_t)bh * Nb + qb;
   const int cnt = min(kept_count[row], Nb);
   const int *idx = kept_idx + row * Nb;
 
+  // ---- prologue: first kept block into LDS ---------------------------------------------
+  int j_cur = 0, nvalid_cur = 0;
+  if (cnt > 0) {
+    j_cur = min(max(idx[0], 0), Nb - 1);  // stay in bounds whatever the list holds
+    nvalid_cur = min(BLK, N - j_cur * BLK);
+    const KStage<KCH> kst = load_k(j_cur * BLK, nvalid_cur);
+    store_k(kst);
+#pragma unroll
+    for (int hh = 0; hh < NH; ++hh) {
+      const KStage<4> vst = load_v(hh, j_cur * BLK, nvalid_cur);
+      store_vt(vst, hh);
+    }
+  }
+  __syncthreads();
+
   for (int c = 0; c < cnt; ++c) {
-    int j = idx[c];
-    j = min(max(j, 0), Nb - 1);  // stay in bounds whatever the list holds
-    const int kv0 = j * BLK;
-    const int nvalid = min(BLK, N - kv0);
+    // After the last kept block the "next" block is the current one again: the staging
+    // below then re-stages data nobody reads, which keeps the loop body branch-free.
+    const int j_next = min(max(idx[min(c + 1, cnt - 1)], 0), Nb - 1);
+    const int nvalid_next = min(BLK, N - j_next * BLK);
 
-    __syncthreads();  // every wave is done reading the previous tiles
-    // ---- K tile -> LDS ------------------------------------------------------------
-#pragma unroll
-    for (int it = 0; it < (BLK * CPR) / NT; ++it) {
-      const int ch = t + it * NT;
-      const int r = ch / CPR, c8 = ch % CPR;
-      uint4 g = make_uint4(0u, 0u, 0u, 0u);
-      if (r < nvalid)
-        g = *reinterpret_cast<const uint4 *>(kbase + (long long)(kv0 + r) * ksn + c8 * 8);
-      *reinterpret_cast<uint4 *>(sK + r * SK + c8 * 8) = g;
-    }
-    // ---- V tile -> registers -> transposed -> LDS ----------------------------------
-#pragma unroll
-    for (int it = 0; it < D / 64; ++it) {
-      const int s = (t >> 5) + (NT / 32) * it;
-      const int dg = (t & 3) + 4 * (s % (D / 32));
-      const int kg = ((t & 31) >> 2) + 8 * (s / (D / 32));
-      uint4 vr[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int r = kg * 4 + e;
-        vr[e] = make_uint4(0u, 0u, 0u, 0u);
-        if (r < nvalid)
-          vr[e] = *reinterpret_cast<const uint4 *>(vbase + (long long)(kv0 + r) * vsn + dg * 8);
-      }
-      const uint32_t w[4][4] = {{vr[0].x, vr[0].y, vr[0].z, vr[0].w},
-                                {vr[1].x, vr[1].y, vr[1].z, vr[1].w},
-                                {vr[2].x, vr[2].y, vr[2].z, vr[2].w},
-                                {vr[3].x, vr[3].y, vr[3].z, vr[3].w}};
-#pragma unroll
-      for (int wd = 0; wd < 4; ++wd) {
-        // word wd of key e holds d = 2*wd (low half) and 2*wd+1 (high half)
-        uint2 even, odd;
-        even.x = __builtin_amdgcn_perm(w[1][wd], w[0][wd], 0x05040100u);  // lo16(k0) | lo16(k1)<<16
-        even.y = __builtin_amdgcn_perm(w[3][wd], w[2][wd], 0x05040100u);
-        odd.x = __builtin_amdgcn_perm(w[1][wd], w[0][wd], 0x07060302u);   // hi16(k0) | hi16(k1)<<16
-        odd.y = __builtin_amdgcn_perm(w[3][wd], w[2][wd], 0x07060302u);
-        *reinterpret_cast<uint2 *>(sVT + (dg * 8 + 2 * wd) * SV + kg * 4) = even;
-        *reinterpret_cast<uint2 *>(sVT + (dg * 8 + 2 * wd + 1) * SV + kg * 4) = odd;
-      }
-    }
-    __syncthreads();
+    // K of the next kept block travels to registers while the matrix cores work on this one
+    const KStage<KCH> kreg = load_k(j_next * BLK, nvalid_next);
 
-    // ---- S^T = K Q^T ----------------------------------------------------------------
-    f32x16_t s[KT];
+    KStage<4> vstage[NH];
+    // The key block is processed in NH slices of 64 keys (keeps the S^T and P^T
+    // registers to 32 + 16 per lane); each slice is a full online-softmax update.
 #pragma unroll
-    for (int kt = 0; kt < KT; ++kt) {
+    for (int hh = 0; hh < NH; ++hh) {
+      // ---- S^T = K Q^T for keys [64*hh, 64*hh + 64) -------------------------------------
+      f32x16_t s[KTH];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
+      for (int kt = 0; kt < KTH; ++kt)
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        Frag8 a;
-        a.u = *reinterpret_cast<const uint4 *>(sK + (kt * 32 + l32) * SK + ks * 16 + hf * 8);
-        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, qf[ks].v, s[kt], 0, 0, 0);
+        for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int kt = 0; kt < KTH; ++kt) {
+          Frag8 a;
+          a.u = *reinterpret_cast<const u32x4_t *>(sK + ((hh * KTH + kt) * 32 + l32) * SK +
+                                                 ks * 16 + hf * 8);
+          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, qf[ks].v, s[kt], 0, 0, 0);
+        }
+      if (hh == NH - 1) {
+        // A: every wave is done reading sK and the V^T slices before the last one
+        __syncthreads();
+        store_k(kreg);
+#pragma unroll
+        for (int h2 = 0; h2 < NH - 1; ++h2) store_vt(vstage[h2], h2);
       }
-    }
 
-    // ---- online softmax (per lane = per query column) ---------------------------------
-    float m_loc = -__builtin_inff();
+      // ---- online softmax (per lane = per query column) -------------------------------
+      if (nvalid_cur < BLK) {  // ragged last key block: keys past the end get no weight
 #pragma unroll
-    for (int kt = 0; kt < KT; ++kt)
+        for (int kt = 0; kt < KTH; ++kt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float x = s[kt][r] * scale_log2e;
-        const int key = kt * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-        if (key >= nvalid) x = -__builtin_inff();
-        s[kt][r] = x;
-        m_loc = fmaxf(m_loc, x);
+          for (int r = 0; r < 16; ++r) {
+            const int key = (hh * KTH + kt) * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+            if (key >= nvalid_cur) s[kt][r] = -__builtin_inff();
+          }
       }
-    m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, 64));
-    const float m_new = fmaxf(m_run, m_loc);
-    const float m_safe = m_new == -__builtin_inff() ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-    float psum = 0.f;
-    Frag8 pf[KT][2];
+      float m_loc = s[0][0];
 #pragma unroll
-    for (int kt = 0; kt < KT; ++kt) {
-      float p[16];
+      for (int kt = 0; kt < KTH; ++kt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        p[r] = __builtin_amdgcn_exp2f(s[kt][r] - m_safe);
-        psum += p[r];
+        for (int r = 0; r < 16; r += 2) m_loc = fmaxf(fmaxf(m_loc, s[kt][r]), s[kt][r + 1]);
+      m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, 64));
+      const float m_tile = m_loc * scale_log2e;  // scale > 0, so max commutes with scaling
+      // The reference exponent only moves when the slice maximum exceeds it by more
+      // than the slack: exponentials then stay below 2^slack, and the rescale of the
+      // accumulators is skipped for most slices.  (A slice whose keys are all past the
+      // end has m_tile = -inf and never bumps.)
+      const bool bump = m_tile > m_ref + kRescaleSlack ||
+                        (m_ref == -__builtin_inff() && m_tile > -__builtin_inff());
+      if (__any(bump)) {
+        const float m_new = bump ? m_tile : m_ref;
+        const float alpha = bump ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.f;
+        l_run *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+        m_ref = m_new;
       }
+      // while m_ref is still -inf every logit seen so far was masked: weights are 0
+      const float m_sub = m_ref == -__builtin_inff() ? 0.f : m_ref;
+      float psum = 0.f;
+      Frag8 pf[KTH][2];
 #pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
-        pf[kt][s2].u.x = cvt_pk_bf16(p[8 * s2 + 0], p[8 * s2 + 1]);
-        pf[kt][s2].u.y = cvt_pk_bf16(p[8 * s2 + 2], p[8 * s2 + 3]);
-        pf[kt][s2].u.z = cvt_pk_bf16(p[8 * s2 + 4], p[8 * s2 + 5]);
-        pf[kt][s2].u.w = cvt_pk_bf16(p[8 * s2 + 6], p[8 * s2 + 7]);
-      }
-    }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
+      for (int kt = 0; kt < KTH; ++kt) {
+        float p[16];
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
-
-    // ---- O^T += V^T P^T -----------------------------------------------------------------
-    // slot e of pf[kt][s2] is key kt*32 + 16*s2 + 8*(e/4) + 4*hf + e%4
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int kt = 0; kt < KT; ++kt)
+        for (int r = 0; r < 16; ++r) {
+          p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kt][r], scale_log2e, -m_sub));
+          psum += p[r];
+        }
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-          const uint16_t *vp = sVT + (dt * 32 + l32) * SV + kt * 32 + 16 * s2 + 4 * hf;
-          Frag8 a;
-          a.h[0] = *reinterpret_cast<const uint2 *>(vp);
-          a.h[1] = *reinterpret_cast<const uint2 *>(vp + 8);
-          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, pf[kt][s2].v, o[dt], 0, 0, 0);
+          pf[kt][s2].u.x = cvt_pk_bf16(p[8 * s2 + 0], p[8 * s2 + 1]);
+          pf[kt][s2].u.y = cvt_pk_bf16(p[8 * s2 + 2], p[8 * s2 + 3]);
+          pf[kt][s2].u.z = cvt_pk_bf16(p[8 * s2 + 4], p[8 * s2 + 5]);
+          pf[kt][s2].u.w = cvt_pk_bf16(p[8 * s2 + 6], p[8 * s2 + 7]);
         }
+      }
+      l_run += psum;
+
+      // slice hh of the next V travels to registers during this slice's second contraction
+      vstage[hh] = load_v(hh, j_next * BLK, nvalid_next);
+
+      // ---- O^T += V^T P^T ---------------------------------------------------------------
+      // slot e of pf[kt][s2] is key (hh*KTH+kt)*32 + 16*s2 + 8*(e/4) + 4*hf + e%4
+#pragma unroll
+      for (int kt = 0; kt < KTH; ++kt)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) {
+            const uint16_t *vp =
+                sVT + (dt * 32 + l32) * SV + (hh * KTH + kt) * 32 + 16 * s2 + 4 * hf;
+            Frag8 a;
+            a.h[0] = *reinterpret_cast<const u32x2_t *>(vp);
+            a.h[1] = *reinterpret_cast<const u32x2_t *>(vp + 8);
+            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, pf[kt][s2].v, o[dt], 0, 0, 0);
+          }
+    }
+    // B: every wave is done with the last V^T slice; the new sK and the earlier V^T
+    // slices are visible.  The last slice written below is read only after the next A.
+    __syncthreads();
+    store_vt(vstage[NH - 1], NH - 1);
+    j_cur = j_next;
+    nvalid_cur = nvalid_next;
   }
 
   // ---- epilogue: normalise, stage through LDS, coalesced bf16 store -----------------------
@@ -244,28 +348,26 @@ __global__ __launch_bounds__(BLK * 2) void attn_kernel(
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   if (lse && hf == 0 && qrow < N)
     lse[(size_t)bh * N + qrow] =
-        l_tot > 0.f ? (m_run + log2f(l_tot)) * 0.6931471805599453f : -__builtin_inff();
-  __syncthreads();  // all waves finished with sK / sVT
-  uint16_t *sO = sK;  // [BLK][SK]
+        l_tot > 0.f ? (m_ref + log2f(l_tot)) * 0.6931471805599453f : -__builtin_inff();
+  uint16_t *sO = sK;  // [BLK][SK]; sK is idle after the last barrier
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      uint2 pk;
+      u32x2_t pk;
       pk.x = cvt_pk_bf16(o[dt][4 * g + 0] * inv, o[dt][4 * g + 1] * inv);
       pk.y = cvt_pk_bf16(o[dt][4 * g + 2] * inv, o[dt][4 * g + 3] * inv);
-      *reinterpret_cast<uint2 *>(sO + (wave * 32 + l32) * SK + dt * 32 + 8 * g + 4 * hf) = pk;
+      *reinterpret_cast<u32x2_t *>(sO + (wave * 32 + l32) * SK + dt * 32 + 8 * g + 4 * hf) = pk;
     }
   __syncthreads();
   uint16_t *obase = out + b * osb + h * osh;
 #pragma unroll
-  for (int it = 0; it < (BLK * CPR) / NT; ++it) {
-    const int ch = t + it * NT;
-    const int r = ch / CPR, c8 = ch % CPR;
+  for (int it = 0; it < KCH; ++it) {
+    const int r = k_r0 + it * K_R_STEP;
     const int n = qb * BLK + r;
     if (n < N)
-      *reinterpret_cast<uint4 *>(obase + (long long)n * osn + c8 * 8) =
-          *reinterpret_cast<const uint4 *>(sO + r * SK + c8 * 8);
+      *reinterpret_cast<u32x4_t *>(obase + (long long)n * osn + k_c) =
+          *reinterpret_cast<const u32x4_t *>(sO + r * SK + k_c);
   }
 }
 
