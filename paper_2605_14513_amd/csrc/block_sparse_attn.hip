@@ -90,7 +90,6 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_kernel(
     const int *__restrict__ kept_idx, const int *__restrict__ kept_count, float scale_log2e,
     float *__restrict__ lse) {
   constexpr int NT = BLK * 2;            // threads
-  constexpr int KT = BLK / 32;           // 32-key tiles per key block
   constexpr int DT = D / 32;             // 32-wide d tiles of the output
   constexpr int KS = D / 16;             // k-steps of the first contraction
   constexpr int SK = D + 8;              // LDS row stride of the K tile (elements)
@@ -100,8 +99,6 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_kernel(
   constexpr int K_R_STEP = NT / CPR;     // rows between a thread's K chunks
   constexpr int VIT = D / 64;            // V sub-tiles (4 keys x 8 d) per thread
   constexpr int V_KG_STEP = 8 * ((NT / 32) / (D / 32));  // key groups between them
-  constexpr int KTH = 2;                 // 32-key tiles per slice of the key block
-  constexpr int NH = KT / KTH;           // slices per key block
   constexpr float kRescaleSlack = 8.f;   // log2 units the running reference may lag the max
 
   extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -142,55 +139,44 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_kernel(
   const int v_kg0 = ((t & 31) >> 2) + 8 * ((t >> 5) / (D / 32));
   const uint32_t v_off0 = (uint32_t)(v_kg0 * 4) * v_row_bytes + (uint32_t)v_dg * 16u;
 
-  auto load_k = [&](int kv0) -> Stage<KCH> {
-    Stage<KCH> st;
-    uint32_t off = k_off0 + (uint32_t)kv0 * k_row_bytes;
-#pragma unroll
-    for (int it = 0; it < KCH; ++it) {
-      st.r[it] = __builtin_amdgcn_raw_buffer_load_b128(k_rs, off, 0, 0);
-      off += K_R_STEP * k_row_bytes;
-    }
-    return st;
+  // Staging is written per operation so that the loop can issue the loads and LDS
+  // stores one at a time in the shadow of MFMAs instead of in bursts after a barrier.
+  // K: chunk `it` (0 .. KCH-1) of this thread.
+  auto load_k1 = [&](Stage<KCH> &st, int it, int kv0) {
+    st.r[it] = __builtin_amdgcn_raw_buffer_load_b128(
+        k_rs, k_off0 + (uint32_t)(kv0 + it * K_R_STEP) * k_row_bytes, 0, 0);
   };
-  auto store_k = [&](const Stage<KCH> &st) {
-    uint16_t *dst = sK + k_r0 * SK + k_c;
-#pragma unroll
-    for (int it = 0; it < KCH; ++it)
-      *reinterpret_cast<u32x4_t *>(dst + it * K_R_STEP * SK) = st.r[it];
+  auto store_k1 = [&](const Stage<KCH> &st, int it) {
+    *reinterpret_cast<u32x4_t *>(sK + (k_r0 + it * K_R_STEP) * SK + k_c) = st.r[it];
   };
-  auto load_v = [&](int kv0) -> Stage<VIT * 4> {
-    Stage<VIT * 4> st;
-    uint32_t off = v_off0 + (uint32_t)kv0 * v_row_bytes;
-#pragma unroll
-    for (int it = 0; it < VIT; ++it) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        st.r[it * 4 + e] = __builtin_amdgcn_raw_buffer_load_b128(v_rs, off + e * v_row_bytes, 0, 0);
-      off += V_KG_STEP * 4 * v_row_bytes;
-    }
-    return st;
+  // V: the tile is staged in two halves of BLK/2 keys.  Sub-tile `it` of this thread lies
+  // in half (v_kg0 + it * V_KG_STEP) / KGH: with VIT == 2 that is `it`, with VIT == 1 it is
+  // uniform per wavefront.  Each sub-tile is 4 loads (keys) and 4 transposed word pairs.
+  constexpr int KGH = BLK / 8;  // key groups (of 4 keys) per half
+  static_assert(VIT == 1 || (VIT == 2 && V_KG_STEP == KGH), "V staging layout");
+  auto v_half_of = [&](int it) -> int { return (v_kg0 + it * V_KG_STEP) / KGH; };
+  auto load_v1 = [&](Stage<4> &st, int it, int e, int kv0) {
+    st.r[e] = __builtin_amdgcn_raw_buffer_load_b128(
+        v_rs, v_off0 + (uint32_t)(kv0 + it * V_KG_STEP * 4 + e) * v_row_bytes, 0, 0);
   };
-  auto store_vt = [&](const Stage<VIT * 4> &st) {
-#pragma unroll
-    for (int it = 0; it < VIT; ++it) {
-      const u32x4_t *vr = st.r + it * 4;
-      // 4-key chunk c of a 16-key group is stored at chunk position (0,2,1,3)[c]
-      const int kg = v_kg0 + it * V_KG_STEP;
-      const int pos = (kg & ~3) | ((kg & 1) << 1) | ((kg >> 1) & 1);
-      uint16_t *dst = sVT + (v_dg * 8) * SV + pos * 4;
-#pragma unroll
-      for (int wd = 0; wd < 4; ++wd) {
-        // word wd of key e holds d = 2*wd (low half) and d = 2*wd+1 (high half)
-        u32x2_t even, odd;
-        even.x = __builtin_amdgcn_perm(vr[1][wd], vr[0][wd], 0x05040100u);  // lo16(k0) | lo16(k1)<<16
-        even.y = __builtin_amdgcn_perm(vr[3][wd], vr[2][wd], 0x05040100u);
-        odd.x = __builtin_amdgcn_perm(vr[1][wd], vr[0][wd], 0x07060302u);   // hi16(k0) | hi16(k1)<<16
-        odd.y = __builtin_amdgcn_perm(vr[3][wd], vr[2][wd], 0x07060302u);
-        *reinterpret_cast<u32x2_t *>(dst + (2 * wd) * SV) = even;
-        *reinterpret_cast<u32x2_t *>(dst + (2 * wd + 1) * SV) = odd;
-      }
-    }
+  // word pair wd (d = 2wd, 2wd+1) of the 4 keys of sub-tile `it`
+  auto store_vt1 = [&](const Stage<4> &st, int it, int wd) {
+    // 4-key chunk c of a 16-key group is stored at chunk position (0,2,1,3)[c]
+    const int kg = v_kg0 + it * V_KG_STEP;
+    const int pos = (kg & ~3) | ((kg & 1) << 1) | ((kg >> 1) & 1);
+    uint16_t *dst = sVT + (v_dg * 8 + 2 * wd) * SV + pos * 4;
+    u32x2_t even, odd;
+    even.x = __builtin_amdgcn_perm(st.r[1][wd], st.r[0][wd], 0x05040100u);  // lo16(k0) | lo16(k1)<<16
+    even.y = __builtin_amdgcn_perm(st.r[3][wd], st.r[2][wd], 0x05040100u);
+    odd.x = __builtin_amdgcn_perm(st.r[1][wd], st.r[0][wd], 0x07060302u);   // hi16(k0) | hi16(k1)<<16
+    odd.y = __builtin_amdgcn_perm(st.r[3][wd], st.r[2][wd], 0x07060302u);
+    *reinterpret_cast<u32x2_t *>(dst) = even;
+    *reinterpret_cast<u32x2_t *>(dst + SV) = odd;
   };
+  // Whole-half helpers.  `mine(half)`: does this thread stage anything of that half?
+  // (VIT == 2: always, sub-tile it == half; VIT == 1: only if its sub-tile lies there.)
+  auto v_it_of = [&](int half) -> int { return VIT == 2 ? half : 0; };
+  auto v_mine = [&](int half) -> bool { return VIT == 2 ? true : v_half_of(0) == half; };
 
   // ---- Q fragments (B operand of S^T = K Q^T), kept in registers ----------------
   const int qrow = qb * BLK + wave * 32 + l32;
@@ -221,10 +207,19 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_kernel(
   if (cnt > 0) {
     j_cur = kept(0);
     j_next = kept(1);
-    const Stage<KCH> kst = load_k(j_cur * BLK);
-    const Stage<VIT * 4> vst = load_v(j_cur * BLK);
-    store_k(kst);
-    store_vt(vst);
+    Stage<KCH> kst;
+#pragma unroll
+    for (int it = 0; it < KCH; ++it) load_k1(kst, it, j_cur * BLK);
+#pragma unroll
+    for (int it = 0; it < KCH; ++it) store_k1(kst, it);
+#pragma unroll
+    for (int it = 0; it < VIT; ++it) {
+      Stage<4> vst;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) load_v1(vst, it, e, j_cur * BLK);
+#pragma unroll
+      for (int wd = 0; wd < 4; ++wd) store_vt1(vst, it, wd);
+    }
   }
   __syncthreads();
 
@@ -232,112 +227,218 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_kernel(
   const uint16_t *sK_rd = sK + l32 * SK + hf * 8;
   const uint16_t *sV_rd = sVT + l32 * SV + hf * 8;
 
+  // ---- the loop over kept key blocks --------------------------------------------------------
+  // A key block is consumed in NSL slices of 32 keys, software-pipelined; the instruction
+  // order written here is the intended issue order (fenced with sched_barrier):
+  //   B(sl)  MFMAs of S^T(sl+1); after each: one LDS fragment read for a later MFMA, the
+  //          exponentials / bf16 rounding / row sum of a few elements of slice sl, and
+  //          at most one staging operation                                (MFMA || VALU)
+  //   C(sl)  MFMAs of O^T += V^T P^T(sl); after each: one LDS fragment read, part of the
+  //          maximum of S^T(sl+1), at most one staging operation          (MFMA || VALU)
+  //   then the (rare) move of the reference exponent.
+  // Staging of the next key block, spread over these slots:
+  //   K loads and V loads of half 0 in B(0); V loads of half 1 in C(NSL-2)
+  //   barrier A after B(NSL-2): every wave has read all of sK and V^T half 0
+  //   K stores and V^T half-0 stores in C(NSL-2)
+  //   barrier B after C(NSL-1): every wave has read V^T half 1; new sK / half 0 visible
+  //   V^T half-1 stores in W = S^T(slice 0) of the next block; first read after the next A
+  constexpr int NSL = BLK / 32;           // slices per key block
+  constexpr int PF = KS < 4 ? KS : 4;     // LDS fragment reads in flight ahead of the MFMAs
+  constexpr int EPM = 16 / KS;            // softmax elements handled per S^T MFMA
+  constexpr int NPV = 2 * DT;             // MFMAs of one slice's O^T update
+  static_assert(16 % KS == 0 && (NSL == 2 || NSL == 4), "slice layout");
+
+  auto kfrag = [&](int sl, int ks) -> u32x4_t {
+    return *reinterpret_cast<const u32x4_t *>(sK_rd + sl * 32 * SK + ks * 16);
+  };
+  // 8 keys of slice sl for MFMA m (s2 = m / DT, d tile m % DT): key positions
+  // sl*32 + 16*s2 + 8*hf .. +7 (see header)
+  auto vfrag = [&](int sl, int m) -> u32x4_t {
+    return *reinterpret_cast<const u32x4_t *>(sV_rd + (m % DT) * 32 * SV + sl * 32 + 16 * (m / DT));
+  };
+
+  f32x16_t sacc[2];  // S^T of the slice being exponentiated and of the next one
+  Frag8 pf[2];       // P^T of the current slice: [s2] = rows 8*s2 .. 8*s2+7 of the accumulator
+
+  // B: S^T(slice sl) into sacc[sl & 1]; with_exp: interleave the weights of slice sl-1
+  // (relative to the reference exponent, rounded to bf16; the row sum adds the ROUNDED
+  // weights, the ones the second contraction uses).  extra(slot) injects staging work.
+  auto qk_step = [&](int sl, bool with_exp, float m_sub, auto &&extra) {
+    f32x16_t acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    const f32x16_t &prev = sacc[(sl + 1) & 1];
+    Frag8 fa[PF];
+#pragma unroll
+    for (int j = 0; j < PF; ++j) fa[j].u = kfrag(sl, j);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks % PF].v, qf[ks].v, acc, 0, 0, 0);
+      if (ks + PF < KS) fa[ks % PF].u = kfrag(sl, ks + PF);
+      if (with_exp) {
+#pragma unroll
+        for (int e = 0; e < EPM; e += 2) {
+          const int r = ks * EPM + e;
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(prev[r], scale_log2e, -m_sub));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(prev[r + 1], scale_log2e, -m_sub));
+          const uint32_t pk = cvt_pk_bf16(p0, p1);
+          pf[r / 8].u[(r % 8) / 2] = pk;
+          l_run = add_bf16_pair(pk, l_run);
+        }
+      }
+      extra(ks);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    sacc[sl & 1] = acc;
+  };
+  // the weights alone (last slice of a key block: no S^T left to overlap with)
+  auto exp_only = [&](int sl, float m_sub) {
+    const f32x16_t &cur = sacc[sl & 1];
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) {
+      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[r], scale_log2e, -m_sub));
+      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[r + 1], scale_log2e, -m_sub));
+      const uint32_t pk = cvt_pk_bf16(p0, p1);
+      pf[r / 8].u[(r % 8) / 2] = pk;
+      l_run = add_bf16_pair(pk, l_run);
+    }
+  };
+  // keys past the end of a ragged last key block get no weight
+  auto mask_slice = [&](f32x16_t &x, int sl, int nvalid) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int key = sl * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+      if (key >= nvalid) x[r] = -__builtin_inff();
+    }
+  };
+  // maximum of one accumulator over this lane's 16 keys, in MAXP partial steps so that
+  // it can be spread over MFMA slots; step i folds elements 4i .. 4i+3
+  auto max_part = [&](const f32x16_t &x, int i, float m) -> float {
+    return fmaxf(fmaxf(fmaxf(m, x[4 * i]), fmaxf(x[4 * i + 1], x[4 * i + 2])), x[4 * i + 3]);
+  };
+  // Finish the maximum of a slice (combine the two lanes of a query: lane l and l^32 are
+  // exchanged with one v_permlane32_swap) and, rarely, move the reference exponent.
+  // The reference only moves when the slice maximum exceeds it by more than the slack:
+  // exponentials then stay below 2^slack and the accumulator rescale is skipped for
+  // most slices.  A slice whose keys are all past the end has maximum -inf and never
+  // moves it.  Returns the exponent to subtract (0 while every logit so far was masked).
+  auto finish_max = [&](float m_loc) -> float {
+    const uint32_t mi = __float_as_uint(m_loc);
+    const auto sw = __builtin_amdgcn_permlane32_swap(mi, mi, false, false);
+    m_loc = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+    const float m_tile = m_loc * scale_log2e;  // scale > 0, so max commutes with scaling
+    const bool bump = m_tile > m_ref + kRescaleSlack ||
+                      (m_ref == -__builtin_inff() && m_tile > -__builtin_inff());
+    if (__any(bump)) {
+      const float m_new = bump ? m_tile : m_ref;
+      const float alpha = bump ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.f;
+      l_run *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+      m_ref = m_new;
+    }
+    return m_ref == -__builtin_inff() ? 0.f : m_ref;
+  };
+  // C: O^T += V^T P^T(slice sl); the second half of the MFMA slots also folds the maximum
+  // of `nxt` (S^T of the following slice, whose MFMAs were issued before this step and
+  // have drained by then).  Returns that lane-local maximum.
+  auto pv_step = [&](int sl, bool nxt, auto &&extra) -> float {
+    const f32x16_t &nx = sacc[(sl + 1) & 1];
+    float m_loc = -__builtin_inff();
+    Frag8 fv[PF];
+#pragma unroll
+    for (int j = 0; j < PF; ++j) fv[j].u = vfrag(sl, j);
+#pragma unroll
+    for (int m = 0; m < NPV; ++m) {
+      o[m % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[m % PF].v, pf[m / DT].v, o[m % DT], 0, 0, 0);
+      if (m + PF < NPV) fv[m % PF].u = vfrag(sl, m + PF);
+      if (nxt) {
+        // 4 partial steps in the last slots
+        constexpr int first = NPV >= 4 ? NPV - 4 : 0;
+        if (NPV >= 4) {
+          if (m >= first) m_loc = max_part(nx, m - first, m_loc);
+        } else if (m == NPV - 1) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) m_loc = max_part(nx, i, m_loc);
+        }
+      }
+      extra(m);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    return m_loc;
+  };
+  auto no_extra = [](int) {};
+
+  float m_sub = 0.f;
+  if (cnt > 0) {
+    qk_step(0, false, 0.f, no_extra);
+    const int nvalid0 = min(BLK, N - j_cur * BLK);
+    if (nvalid0 < BLK) mask_slice(sacc[0], 0, nvalid0);
+    float m_loc = -__builtin_inff();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) m_loc = max_part(sacc[0], i, m_loc);
+    m_sub = finish_max(m_loc);
+  }
   for (int c = 0; c < cnt; ++c) {
     // After the last kept block the "next" block is the current one again: the staging
-    // below then re-stages data nobody reads, which keeps the loop body branch-free.
+    // then re-stages data nobody reads, which keeps the loop branch-free.
     const int j_next2 = kept(c + 2);
     const int nvalid_cur = min(BLK, N - j_cur * BLK);
-
-    // K of the next kept block travels to registers while the matrix cores work on this one
-    const Stage<KCH> kreg = load_k(j_next * BLK);
-    Stage<VIT * 4> vreg;
-
-    // The key block is processed in NH slices of 64 keys (keeps the S^T and P^T
-    // registers to 32 + 16 per lane); each slice is a full online-softmax update.
+    const int nvalid_next = min(BLK, N - j_next * BLK);
+    const int kv_next = j_next * BLK;
+    Stage<KCH> kreg;
+    Stage<4> v0, v1;  // V sub-tiles of half 0 and half 1 of the next key block
 #pragma unroll
-    for (int hh = 0; hh < NH; ++hh) {
-      // ---- S^T = K Q^T for keys [64*hh, 64*hh + 64) -------------------------------------
-      f32x16_t s[KTH];
+    for (int sl = 0; sl < NSL; ++sl) {
+      // ---- B(sl) ----
+      if (sl + 1 < NSL) {
+        qk_step(sl + 1, true, m_sub, [&](int ks) {
+          if (sl == 0) {  // K loads and V half-0 loads of the next key block, spread over the slots
 #pragma unroll
-      for (int kt = 0; kt < KTH; ++kt)
+            for (int it = 0; it < KCH; ++it)
+              if (it * KS / KCH == ks) load_k1(kreg, it, kv_next);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
+            for (int e = 0; e < 4; ++e)
+              if (e * KS / 4 == ks && v_mine(0)) load_v1(v0, v_it_of(0), e, kv_next);
+          }
+        });
+        if (nvalid_cur < BLK) mask_slice(sacc[(sl + 1) & 1], sl + 1, nvalid_cur);
+      } else {
+        exp_only(sl, m_sub);
+      }
+      if (sl == NSL - 2) __syncthreads();  // barrier A
+      // ---- C(sl) ----
+      const float m_loc = pv_step(sl, sl + 1 < NSL, [&](int m) {
+        if (sl == NSL - 2) {
+          // K stores, spread; V^T half-0 stores (one word pair per slot); V loads, half 1
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-        for (int kt = 0; kt < KTH; ++kt) {
-          Frag8 a;
-          a.u = *reinterpret_cast<const u32x4_t *>(sK_rd + (hh * KTH + kt) * 32 * SK + ks * 16);
-          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, qf[ks].v, s[kt], 0, 0, 0);
+          for (int it = 0; it < KCH; ++it)
+            if (it * NPV / KCH == m) store_k1(kreg, it);
+          if (m < 4 && v_mine(0)) store_vt1(v0, v_it_of(0), m);
+          if (m >= NPV - 4 && v_mine(1)) load_v1(v1, v_it_of(1), m - (NPV - 4), kv_next);
         }
-      if (hh == NH - 1) {
-        __syncthreads();  // A: every wave is done reading sK
-        store_k(kreg);
-        vreg = load_v(j_next * BLK);  // in flight during the rest of this key block
-      }
-
-      // ---- online softmax (per lane = per query column) -------------------------------
-      if (nvalid_cur < BLK) {  // ragged last key block: keys past the end get no weight
-#pragma unroll
-        for (int kt = 0; kt < KTH; ++kt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = (hh * KTH + kt) * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-            if (key >= nvalid_cur) s[kt][r] = -__builtin_inff();
-          }
-      }
-      float m_loc = s[0][0];
-#pragma unroll
-      for (int kt = 0; kt < KTH; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; r += 2) m_loc = fmaxf(fmaxf(m_loc, s[kt][r]), s[kt][r + 1]);
-      m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, 64));
-      const float m_tile = m_loc * scale_log2e;  // scale > 0, so max commutes with scaling
-      // The reference exponent only moves when the slice maximum exceeds it by more
-      // than the slack: exponentials then stay below 2^slack, and the rescale of the
-      // accumulators is skipped for most slices.  (A slice whose keys are all past the
-      // end has m_tile = -inf and never bumps.)
-      const bool bump = m_tile > m_ref + kRescaleSlack ||
-                        (m_ref == -__builtin_inff() && m_tile > -__builtin_inff());
-      if (__any(bump)) {
-        const float m_new = bump ? m_tile : m_ref;
-        const float alpha = bump ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.f;
-        l_run *= alpha;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
-        m_ref = m_new;
-      }
-      // while m_ref is still -inf every logit seen so far was masked: weights are 0
-      const float m_sub = m_ref == -__builtin_inff() ? 0.f : m_ref;
-      Frag8 pf[KTH][2];
-#pragma unroll
-      for (int kt = 0; kt < KTH; ++kt) {
-        float p[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kt][r], scale_log2e, -m_sub));
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            const uint32_t pk = cvt_pk_bf16(p[8 * s2 + 2 * w], p[8 * s2 + 2 * w + 1]);
-            pf[kt][s2].u[w] = pk;
-            // the row sum adds the ROUNDED weights, the ones the second contraction uses
-            l_run = add_bf16_pair(pk, l_run);
-          }
-      }
-
-      // ---- O^T += V^T P^T ---------------------------------------------------------------
-      // slot e of pf[kt][s2] is key (hh*KTH+kt)*32 + 16*s2 + 8*(e/4) + 4*hf + e%4; in LDS
-      // these 8 keys are the 16 bytes at key position (hh*KTH+kt)*32 + 16*s2 + 8*hf
-#pragma unroll
-      for (int kt = 0; kt < KTH; ++kt)
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt) {
-            Frag8 a;
-            a.u = *reinterpret_cast<const u32x4_t *>(sV_rd + dt * 32 * SV +
-                                                     (hh * KTH + kt) * 32 + 16 * s2);
-            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, pf[kt][s2].v, o[dt], 0, 0, 0);
-          }
+      });
+      if (sl + 1 < NSL) m_sub = finish_max(m_loc);
     }
-    // B: every wave is done reading sVT; the new sK is visible.  The V^T tile written
-    // below is read only after the next barrier A.
+    // barrier B
     __syncthreads();
-    store_vt(vreg);
+    // ---- W: S^T(slice 0) of the next key block, with the V^T half-1 stores ----
+    qk_step(0, false, 0.f, [&](int ks) {
+      if (ks < 4 && v_mine(1)) store_vt1(v1, v_it_of(1), ks);
+    });
+    if (KS < 4 && v_mine(1)) {
+#pragma unroll
+      for (int wd = KS; wd < 4; ++wd) store_vt1(v1, v_it_of(1), wd);
+    }
+    {
+      if (nvalid_next < BLK) mask_slice(sacc[0], 0, nvalid_next);
+      float m_loc = -__builtin_inff();
+#pragma unroll
+      for (int i = 0; i < 4; ++i) m_loc = max_part(sacc[0], i, m_loc);
+      m_sub = finish_max(m_loc);
+    }
     j_cur = j_next;
     j_next = j_next2;
   }
