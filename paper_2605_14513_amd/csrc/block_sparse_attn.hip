@@ -62,12 +62,6 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, b);
 }
 
-// acc + lo + hi of a packed bf16 pair (one v_dot2 against the constant (1, 1))
-__device__ __forceinline__ float add_bf16_pair(uint32_t pk, float acc) {
-  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pk),
-                                         __builtin_bit_cast(bf16x2_t, 0x3f803f80u), acc, false);
-}
-
 // registers that carry one thread's share of a K or V tile from global memory to LDS
 template <int n>
 struct Stage {
@@ -80,9 +74,15 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t head_rsrc(const uint16_t *base
 }
 
 constexpr int kNumXcd = 8;
+#ifndef HEART_ATTN_PF
+#define HEART_ATTN_PF 4
+#endif
+#ifndef HEART_ATTN_OCC
+#define HEART_ATTN_OCC 2  // waves per SIMD the register budget is sized for
+#endif
 
 template <int D, int BLK>
-__global__ __launch_bounds__(BLK * 2, 2) void attn_kernel(
+__global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k,
     const uint16_t *__restrict__ v, uint16_t *__restrict__ out, long long qsb, long long qsh,
     long long qsn, long long ksb, long long ksh, long long ksn, long long vsb, long long vsh,
@@ -228,80 +228,118 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_kernel(
   const uint16_t *sV_rd = sVT + l32 * SV + hf * 8;
 
   // ---- the loop over kept key blocks --------------------------------------------------------
-  // A key block is consumed in NSL slices of 32 keys, software-pipelined; the instruction
-  // order written here is the intended issue order (fenced with sched_barrier):
-  //   B(sl)  MFMAs of S^T(sl+1); after each: one LDS fragment read for a later MFMA, the
-  //          exponentials / bf16 rounding / row sum of a few elements of slice sl, and
-  //          at most one staging operation                                (MFMA || VALU)
-  //   C(sl)  MFMAs of O^T += V^T P^T(sl); after each: one LDS fragment read, part of the
-  //          maximum of S^T(sl+1), at most one staging operation          (MFMA || VALU)
-  //   then the (rare) move of the reference exponent.
-  // Staging of the next key block, spread over these slots:
-  //   K loads and V loads of half 0 in B(0); V loads of half 1 in C(NSL-2)
-  //   barrier A after B(NSL-2): every wave has read all of sK and V^T half 0
+  // A key block is consumed in NSL slices of 32 keys, software-pipelined.  The MFMAs of one
+  // key block form a fixed stream of SEQ instructions:
+  //   for sl = 0 .. NSL-1:  B(sl): S^T(sl+1), KS MFMAs on K fragments   (not for the last sl)
+  //                         C(sl): O^T += V^T P^T(sl), NPV MFMAs on V^T fragments
+  //   W: S^T(slice 0) of the NEXT key block, KS MFMAs
+  // Every MFMA takes its A operand from a ring of PF registers filled by 16-byte LDS reads
+  // that run PF stream positions ahead, across phase boundaries and across the loop
+  // back-edge; only the two barriers (where the LDS contents change) restart the ring.
+  // The instruction order written here is the intended issue order (sched_barrier fences).
+  // After each MFMA comes a little VALU work that runs in its shadow:
+  //   in B(sl): exponentials / bf16 rounding / row sum of a few elements of slice sl
+  //   in C(sl): part of the maximum of S^T(sl+1); the rare move of the reference exponent
+  //             follows the phase
+  // and at most one staging operation for the next key block:
+  //   K loads and V loads of half 0 in C(0) (in B(0) when NSL == 2); V loads of half 1 in C(NSL-2)
+  //   barrier A before C(NSL-2): every wave has read all of sK and V^T half 0
   //   K stores and V^T half-0 stores in C(NSL-2)
-  //   barrier B after C(NSL-1): every wave has read V^T half 1; new sK / half 0 visible
-  //   V^T half-1 stores in W = S^T(slice 0) of the next block; first read after the next A
+  //   barrier B before W: every wave has read V^T half 1; new sK / half 0 visible
+  //   V^T half-1 stores in W; they are first read after the next barrier A
   constexpr int NSL = BLK / 32;           // slices per key block
-  constexpr int PF = KS < 4 ? KS : 4;     // LDS fragment reads in flight ahead of the MFMAs
   constexpr int EPM = 16 / KS;            // softmax elements handled per S^T MFMA
   constexpr int NPV = 2 * DT;             // MFMAs of one slice's O^T update
-  static_assert(16 % KS == 0 && (NSL == 2 || NSL == 4), "slice layout");
+  constexpr int STEP = KS + NPV;
+  constexpr int G_A = (NSL - 2) * STEP + KS;       // stream position of barrier A: C(NSL-2)
+  constexpr int G_W = (NSL - 1) * STEP + NPV;      // stream position of barrier B: W
+  constexpr int SEQ = G_W + KS;
+  constexpr int PF = HEART_ATTN_PF < KS ? HEART_ATTN_PF : KS;  // LDS reads in flight ahead of the MFMAs
+  static_assert(16 % KS == 0 && (NSL == 2 || NSL == 4) && SEQ % PF == 0 && PF <= KS &&
+                    PF <= NPV, "stream layout");
 
-  auto kfrag = [&](int sl, int ks) -> u32x4_t {
-    return *reinterpret_cast<const u32x4_t *>(sK_rd + sl * 32 * SK + ks * 16);
+  // A-operand fragment of stream position g (g >= SEQ: the next key block's stream)
+  auto fetch = [&](int g) -> u32x4_t {
+    g %= SEQ;
+    const int sl = g / STEP, r = g % STEP;
+    if (sl < NSL - 1) {
+      if (r < KS)  // B(sl): K fragment of slice sl+1, k-step r
+        return *reinterpret_cast<const u32x4_t *>(sK_rd + (sl + 1) * 32 * SK + r * 16);
+      // C(sl): 8 keys of slice sl for MFMA m (s2 = m / DT, d tile m % DT): key positions
+      // sl*32 + 16*s2 + 8*hf .. +7 (see header)
+      const int m = r - KS;
+      return *reinterpret_cast<const u32x4_t *>(sV_rd + (m % DT) * 32 * SV + sl * 32 + 16 * (m / DT));
+    }
+    if (r < NPV)  // C(NSL-1)
+      return *reinterpret_cast<const u32x4_t *>(sV_rd + (r % DT) * 32 * SV + sl * 32 + 16 * (r / DT));
+    return *reinterpret_cast<const u32x4_t *>(sK_rd + (r - NPV) * 16);  // W: slice 0
   };
-  // 8 keys of slice sl for MFMA m (s2 = m / DT, d tile m % DT): key positions
-  // sl*32 + 16*s2 + 8*hf .. +7 (see header)
-  auto vfrag = [&](int sl, int m) -> u32x4_t {
-    return *reinterpret_cast<const u32x4_t *>(sV_rd + (m % DT) * 32 * SV + sl * 32 + 16 * (m / DT));
+  Frag8 ring[PF];
+  // after the MFMA at position g: start the read for position g + PF unless a barrier
+  // lies in between (then the ring is refilled after that barrier)
+  auto prefetch_after = [&](int g) {
+    const int t = g + PF;
+    const bool crosses = (g < G_A && t >= G_A) || (g < G_W && t >= G_W);
+    if (!crosses) ring[t % PF].u = fetch(t);
+  };
+  auto refill = [&](int g0) {
+#pragma unroll
+    for (int j = 0; j < PF; ++j) ring[(g0 + j) % PF].u = fetch(g0 + j);
   };
 
   f32x16_t sacc[2];  // S^T of the slice being exponentiated and of the next one
   Frag8 pf[2];       // P^T of the current slice: [s2] = rows 8*s2 .. 8*s2+7 of the accumulator
 
-  // B: S^T(slice sl) into sacc[sl & 1]; with_exp: interleave the weights of slice sl-1
-  // (relative to the reference exponent, rounded to bf16; the row sum adds the ROUNDED
-  // weights, the ones the second contraction uses).  extra(slot) injects staging work.
-  auto qk_step = [&](int sl, bool with_exp, float m_sub, auto &&extra) {
+  // Weights of one slice relative to the reference exponent, rounded to bf16 for the second
+  // contraction (the row sum adds the unrounded fp32 weights).  The work on the 8
+  // element pairs of a lane is cut into 32 micro-ops of about 8 VALU cycles each (pair
+  // p = u / 4: two FMAs, exponential, exponential, convert + row sum), because only about
+  // 24 cycles of a wave's own VALU work hide behind one of its MFMAs and a slot that
+  // exceeds that stalls the matrix pipeline: B slots take 3 micro-ops, C slots 2.
+  float xt0 = 0.f, xt1 = 0.f;  // the pair in flight
+  auto exp_uop = [&](const f32x16_t &x, int u, float m_sub) {
+    const int r = 2 * (u >> 2), st = u & 3;
+    // (the empty asm statements pin each result to its slot: without them the compiler
+    // sinks the whole computation to its first use, out of the MFMA shadow)
+    if (st == 0) {
+      xt0 = __builtin_fmaf(x[r], scale_log2e, -m_sub);
+      xt1 = __builtin_fmaf(x[r + 1], scale_log2e, -m_sub);
+      asm volatile("" : "+v"(xt0), "+v"(xt1));
+    } else if (st == 1) {
+      xt0 = __builtin_amdgcn_exp2f(xt0);
+      asm volatile("" : "+v"(xt0));
+    } else if (st == 2) {
+      xt1 = __builtin_amdgcn_exp2f(xt1);
+      asm volatile("" : "+v"(xt1));
+    } else {
+      // (plain adds for the row sum: they co-issue with MFMAs, dot instructions do not)
+      uint32_t pk = cvt_pk_bf16(xt0, xt1);
+      l_run += xt0 + xt1;
+      asm volatile("" : "+v"(pk), "+v"(l_run));
+      pf[r / 8].u[(r % 8) / 2] = pk;
+    }
+  };
+  constexpr int UB = 24 / KS;        // micro-ops per B slot: pairs 0..5 of the slice
+  constexpr int UC = 8 / DT;         // micro-ops per C slot m < DT: pairs 6..7
+  // B / W: S^T(slice sl) into sacc[sl & 1], stream positions g0 .. g0+KS-1; with_exp:
+  // interleave the weights of slice sl-1.  extra(slot) injects staging work.
+  auto qk_step = [&](int sl, int g0, bool with_exp, float m_sub, auto &&extra) {
     f32x16_t acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     const f32x16_t &prev = sacc[(sl + 1) & 1];
-    Frag8 fa[PF];
-#pragma unroll
-    for (int j = 0; j < PF; ++j) fa[j].u = kfrag(sl, j);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks % PF].v, qf[ks].v, acc, 0, 0, 0);
-      if (ks + PF < KS) fa[ks % PF].u = kfrag(sl, ks + PF);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[(g0 + ks) % PF].v, qf[ks].v, acc, 0, 0, 0);
+      prefetch_after(g0 + ks);
       if (with_exp) {
 #pragma unroll
-        for (int e = 0; e < EPM; e += 2) {
-          const int r = ks * EPM + e;
-          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(prev[r], scale_log2e, -m_sub));
-          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(prev[r + 1], scale_log2e, -m_sub));
-          const uint32_t pk = cvt_pk_bf16(p0, p1);
-          pf[r / 8].u[(r % 8) / 2] = pk;
-          l_run = add_bf16_pair(pk, l_run);
-        }
+        for (int u = 0; u < UB; ++u) exp_uop(prev, ks * UB + u, m_sub);
       }
       extra(ks);
       __builtin_amdgcn_sched_barrier(0);
     }
     sacc[sl & 1] = acc;
-  };
-  // the weights alone (last slice of a key block: no S^T left to overlap with)
-  auto exp_only = [&](int sl, float m_sub) {
-    const f32x16_t &cur = sacc[sl & 1];
-#pragma unroll
-    for (int r = 0; r < 16; r += 2) {
-      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[r], scale_log2e, -m_sub));
-      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[r + 1], scale_log2e, -m_sub));
-      const uint32_t pk = cvt_pk_bf16(p0, p1);
-      pf[r / 8].u[(r % 8) / 2] = pk;
-      l_run = add_bf16_pair(pk, l_run);
-    }
   };
   // keys past the end of a ragged last key block get no weight
   auto mask_slice = [&](f32x16_t &x, int sl, int nvalid) {
@@ -311,10 +349,11 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_kernel(
       if (key >= nvalid) x[r] = -__builtin_inff();
     }
   };
-  // maximum of one accumulator over this lane's 16 keys, in MAXP partial steps so that
-  // it can be spread over MFMA slots; step i folds elements 4i .. 4i+3
+  // maximum of one accumulator over this lane's 16 keys, in 4 partial steps so that it
+  // can be spread over MFMA slots; step i folds elements 4i .. 4i+3
   auto max_part = [&](const f32x16_t &x, int i, float m) -> float {
-    return fmaxf(fmaxf(fmaxf(m, x[4 * i]), fmaxf(x[4 * i + 1], x[4 * i + 2])), x[4 * i + 3]);
+    m = fmaxf(fmaxf(m, x[4 * i]), x[4 * i + 1]);       // v_max3_f32
+    return fmaxf(fmaxf(m, x[4 * i + 2]), x[4 * i + 3]);  // v_max3_f32
   };
   // Finish the maximum of a slice (combine the two lanes of a query: lane l and l^32 are
   // exchanged with one v_permlane32_swap) and, rarely, move the reference exponent.
@@ -341,28 +380,25 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_kernel(
     }
     return m_ref == -__builtin_inff() ? 0.f : m_ref;
   };
-  // C: O^T += V^T P^T(slice sl); the second half of the MFMA slots also folds the maximum
-  // of `nxt` (S^T of the following slice, whose MFMAs were issued before this step and
-  // have drained by then).  Returns that lane-local maximum.
-  auto pv_step = [&](int sl, bool nxt, auto &&extra) -> float {
-    const f32x16_t &nx = sacc[(sl + 1) & 1];
+  // C: O^T += V^T P^T(slice sl), stream positions g0 .. g0+NPV-1.  The first DT slots
+  // finish the weights of the slice (pairs 6..7, consumed by the second half of the
+  // MFMAs); with_max: the second half of the slots folds the maximum of S^T(sl+1), whose
+  // MFMAs were issued before this phase and have drained by then.
+  auto pv_step = [&](int sl, int g0, bool with_max, float m_sub, auto &&extra) -> float {
     float m_loc = -__builtin_inff();
-    Frag8 fv[PF];
-#pragma unroll
-    for (int j = 0; j < PF; ++j) fv[j].u = vfrag(sl, j);
+    const f32x16_t &nx = sacc[(sl + 1) & 1];
+    const f32x16_t &cur = sacc[sl & 1];
 #pragma unroll
     for (int m = 0; m < NPV; ++m) {
-      o[m % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[m % PF].v, pf[m / DT].v, o[m % DT], 0, 0, 0);
-      if (m + PF < NPV) fv[m % PF].u = vfrag(sl, m + PF);
-      if (nxt) {
-        // 4 partial steps in the last slots
-        constexpr int first = NPV >= 4 ? NPV - 4 : 0;
-        if (NPV >= 4) {
-          if (m >= first) m_loc = max_part(nx, m - first, m_loc);
-        } else if (m == NPV - 1) {
+      o[m % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[(g0 + m) % PF].v, pf[m / DT].v, o[m % DT], 0, 0, 0);
+      prefetch_after(g0 + m);
+      if (m < DT) {
 #pragma unroll
-          for (int i = 0; i < 4; ++i) m_loc = max_part(nx, i, m_loc);
-        }
+        for (int u = 0; u < UC; ++u) exp_uop(cur, 24 + m * UC + u, m_sub);
+      }
+      if (with_max && m >= DT) {
+#pragma unroll
+        for (int i = 0; i < 4 / DT; ++i) m_loc = max_part(nx, (m - DT) * (4 / DT) + i, m_loc);
       }
       extra(m);
       __builtin_amdgcn_sched_barrier(0);
@@ -370,16 +406,20 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_kernel(
     return m_loc;
   };
   auto no_extra = [](int) {};
-
-  float m_sub = 0.f;
-  if (cnt > 0) {
-    qk_step(0, false, 0.f, no_extra);
-    const int nvalid0 = min(BLK, N - j_cur * BLK);
-    if (nvalid0 < BLK) mask_slice(sacc[0], 0, nvalid0);
+  // maximum of slice 0 of a key block right after its S^T (prologue and W)
+  auto slice0_max = [&](int nvalid) -> float {
+    if (nvalid < BLK) mask_slice(sacc[0], 0, nvalid);
     float m_loc = -__builtin_inff();
 #pragma unroll
     for (int i = 0; i < 4; ++i) m_loc = max_part(sacc[0], i, m_loc);
-    m_sub = finish_max(m_loc);
+    return finish_max(m_loc);
+  };
+
+  float m_sub = 0.f;
+  if (cnt > 0) {
+    refill(G_W);
+    qk_step(0, G_W, false, 0.f, no_extra);
+    m_sub = slice0_max(min(BLK, N - j_cur * BLK));
   }
   for (int c = 0; c < cnt; ++c) {
     // After the last kept block the "next" block is the current one again: the staging
@@ -394,8 +434,8 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_kernel(
     for (int sl = 0; sl < NSL; ++sl) {
       // ---- B(sl) ----
       if (sl + 1 < NSL) {
-        qk_step(sl + 1, true, m_sub, [&](int ks) {
-          if (sl == 0) {  // K loads and V half-0 loads of the next key block, spread over the slots
+        qk_step(sl + 1, sl * STEP, true, m_sub, [&](int ks) {
+          if (NSL == 2 && sl == 0) {  // short key blocks: C(0) already stores, so load here
 #pragma unroll
             for (int it = 0; it < KCH; ++it)
               if (it * KS / KCH == ks) load_k1(kreg, it, kv_next);
@@ -406,17 +446,29 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_kernel(
         });
         if (nvalid_cur < BLK) mask_slice(sacc[(sl + 1) & 1], sl + 1, nvalid_cur);
       } else {
-        exp_only(sl, m_sub);
+        // last slice: no S^T left to overlap the first 6 pairs of its weights with
+#pragma unroll
+        for (int u = 0; u < 24; ++u) exp_uop(sacc[sl & 1], u, m_sub);
       }
-      if (sl == NSL - 2) __syncthreads();  // barrier A
+      if (sl == NSL - 2) {
+        __syncthreads();  // barrier A
+        refill(G_A);
+      }
       // ---- C(sl) ----
-      const float m_loc = pv_step(sl, sl + 1 < NSL, [&](int m) {
+      const int g_c = sl * STEP + (sl + 1 < NSL ? KS : 0);
+      const float m_loc = pv_step(sl, g_c, sl + 1 < NSL, m_sub, [&](int m) {
+        if (NSL > 2 && sl == 0) {  // K loads and V half-0 loads of the next key block, spread over the slots
+#pragma unroll
+          for (int it = 0; it < KCH; ++it)
+            if (it * NPV / KCH == m) load_k1(kreg, it, kv_next);
+          if (m >= NPV - 4 && v_mine(0)) load_v1(v0, v_it_of(0), m - (NPV - 4), kv_next);
+        }
         if (sl == NSL - 2) {
           // K stores, spread; V^T half-0 stores (one word pair per slot); V loads, half 1
 #pragma unroll
           for (int it = 0; it < KCH; ++it)
             if (it * NPV / KCH == m) store_k1(kreg, it);
-          if (m < 4 && v_mine(0)) store_vt1(v0, v_it_of(0), m);
+          if (m >= NPV - 4 && v_mine(0)) store_vt1(v0, v_it_of(0), m - (NPV - 4));
           if (m >= NPV - 4 && v_mine(1)) load_v1(v1, v_it_of(1), m - (NPV - 4), kv_next);
         }
       });
@@ -424,21 +476,16 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_kernel(
     }
     // barrier B
     __syncthreads();
+    refill(G_W);
     // ---- W: S^T(slice 0) of the next key block, with the V^T half-1 stores ----
-    qk_step(0, false, 0.f, [&](int ks) {
+    qk_step(0, G_W, false, 0.f, [&](int ks) {
       if (ks < 4 && v_mine(1)) store_vt1(v1, v_it_of(1), ks);
     });
     if (KS < 4 && v_mine(1)) {
 #pragma unroll
       for (int wd = KS; wd < 4; ++wd) store_vt1(v1, v_it_of(1), wd);
     }
-    {
-      if (nvalid_next < BLK) mask_slice(sacc[0], 0, nvalid_next);
-      float m_loc = -__builtin_inff();
-#pragma unroll
-      for (int i = 0; i < 4; ++i) m_loc = max_part(sacc[0], i, m_loc);
-      m_sub = finish_max(m_loc);
-    }
+    m_sub = slice0_max(nvalid_next);
     j_cur = j_next;
     j_next = j_next2;
   }
