@@ -362,9 +362,9 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   // most slices.  A slice whose keys are all past the end has maximum -inf and never
   // moves it.  Returns the exponent to subtract (0 while every logit so far was masked).
   auto finish_max = [&](float m_loc) -> float {
-    const uint32_t mi = __float_as_uint(m_loc);
-    const auto sw = __builtin_amdgcn_permlane32_swap(mi, mi, false, false);
-    m_loc = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+    uint32_t sw0, sw1;
+    swap_halves32(__float_as_uint(m_loc), sw0, sw1);
+    m_loc = fmaxf(__uint_as_float(sw0), __uint_as_float(sw1));
     const float m_tile = m_loc * scale_log2e;  // scale > 0, so max commutes with scaling
     const bool bump = m_tile > m_ref + kRescaleSlack ||
                       (m_ref == -__builtin_inff() && m_tile > -__builtin_inff());

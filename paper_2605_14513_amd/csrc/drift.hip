@@ -2,9 +2,11 @@
 // Reuse (Sec. 4.2; Alg. 1), the layer-level gate (Sec. 4.2; thresholds from the
 // appendix on HEART configurations) and the anchor update.
 //
-// The data is tiny (4*B*H*D floats), so this is one launch with one workgroup per
-// batch item: the gate needs the count of marked heads of that item, and keeping
-// it inside one workgroup avoids any cross-workgroup synchronisation.
+// The data is tiny (4*B*H*D floats), so this is one launch with one workgroup of 16
+// wavefronts per batch item (one head per wavefront and pass): the gate needs the
+// count of marked heads of that item, and keeping it inside one workgroup avoids any
+// cross-workgroup synchronisation.  The kernel is bound by a few dependent memory
+// round trips, not by bandwidth.
 //
 // drift is summed in fp32 with a fixed halving tree over d:
 //   a[d] = |qa[d]-qb[d]| + |ka[d]-kb[d]|;  for s = D/2 .. 1: a[i] += a[i+s] (i < s)
@@ -16,9 +18,10 @@
 
 namespace heart {
 
-constexpr int kMaxSlots = 8;  // D <= 512
+constexpr int kMaxSlots = 8;   // D <= 512
+constexpr int kThreads = 1024; // 16 wavefronts: 16 heads in flight per pass
 
-__global__ __launch_bounds__(256) void drift_kernel(
+__global__ __launch_bounds__(kThreads) void drift_kernel(
     int H, int D, const float *__restrict__ qmean, const float *__restrict__ kmean,
     float *__restrict__ qanchor, float *__restrict__ kanchor,
     unsigned char *__restrict__ has_anchor, const float *__restrict__ delta, float gate_lo,
@@ -32,15 +35,18 @@ __global__ __launch_bounds__(256) void drift_kernel(
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int slots = D > 64 ? D / 64 : 1;
 
-  for (int h = wave; h < H; h += 4) {
+  for (int h = wave; h < H; h += kThreads / 64) {
     size_t o = ((size_t)b * H + h) * D;
-    bool has = has_anchor[(size_t)b * H + h] != 0;
+    // all loads are issued unconditionally (the anchor buffers always exist); a head
+    // without an anchor ignores the value
+    const bool has = has_anchor[(size_t)b * H + h] != 0;
+    const float dl = delta[h];
     float a[kMaxSlots];
 #pragma unroll
     for (int c = 0; c < kMaxSlots; ++c) {
       a[c] = 0.f;
       int d = lane + 64 * c;
-      if (c < slots && d < D && has) {
+      if (c < slots && d < D) {
         float dq = fabsf(qanchor[o + d] - qmean[o + d]);
         float dk = fabsf(kanchor[o + d] - kmean[o + d]);
         a[c] = dq + dk;
@@ -65,14 +71,15 @@ __global__ __launch_bounds__(256) void drift_kernel(
     if (lane == 0) {
       float dv = has ? v : __builtin_inff();
       drift[(size_t)b * H + h] = dv;
-      mark[h] = (!has || dv > delta[h]) ? 1 : 0;
+      mark[h] = (!has || dv > dl) ? 1 : 0;
     }
   }
   __syncthreads();
-  if (threadIdx.x == 0) {
-    int n = 0;
-    for (int h = 0; h < H; ++h) n += mark[h];
-    n_mark_sh = n;
+  if (wave == 0) {
+    uint32_t n = 0;
+    for (int h = lane; h < H; h += 64) n += mark[h];
+    n = wave_sum_u32(n);
+    if (lane == 0) n_mark_sh = (int)n;
   }
   __syncthreads();
   const float frac = __fdiv_rn((float)n_mark_sh, (float)H);
@@ -106,8 +113,8 @@ int launch_drift(int B, int H, int D, const float *qmean, const float *kmean, fl
                  float *kanchor, unsigned char *has_anchor, const float *delta, float gate_lo,
                  float gate_hi, int commit, float *drift, unsigned char *refresh,
                  hipStream_t st) {
-  hipLaunchKernelGGL(drift_kernel, dim3(B), dim3(256), (size_t)2 * H, st, H, D, qmean, kmean,
-                     qanchor, kanchor, has_anchor, delta, gate_lo, gate_hi, commit, drift,
+  hipLaunchKernelGGL(drift_kernel, dim3(B), dim3(kThreads), (size_t)2 * H, st, H, D, qmean,
+                     kmean, qanchor, kanchor, has_anchor, delta, gate_lo, gate_hi, commit, drift,
                      refresh);
   return check_launch("drift_kernel");
 }

@@ -34,6 +34,78 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
 }
 
+// Lane exchanges on the VALU.  v_permlane16_swap / v_permlane32_swap exchange the odd
+// rows (upper half) of their first operand with the even rows (lower half) of the
+// second.  Fed the same value twice they return the pair (r0, r1) with
+//   swap16: r0 = rows (0,0,2,2), r1 = rows (1,1,3,3) of v     (a row is 16 lanes)
+//   swap32: r0 = halves (lo, lo), r1 = halves (hi, hi) of v
+// so OP(r0, r1) combines every lane with its partner row / half, identically on both
+// sides.  The second operand goes through an empty asm so that the compiler cannot
+// see that both operands are the same value (it would then fold r0 and r1 into one).
+__device__ __forceinline__ void swap_rows16(uint32_t v, uint32_t &r0, uint32_t &r1) {
+  uint32_t w = v;
+  asm volatile("" : "+v"(w));
+  const auto r = __builtin_amdgcn_permlane16_swap(v, w, false, false);
+  r0 = r[0];
+  r1 = r[1];
+}
+__device__ __forceinline__ void swap_halves32(uint32_t v, uint32_t &r0, uint32_t &r1) {
+  uint32_t w = v;
+  asm volatile("" : "+v"(w));
+  const auto r = __builtin_amdgcn_permlane32_swap(v, w, false, false);
+  r0 = r[0];
+  r1 = r[1];
+}
+
+// Wave-wide reductions that leave the result in every lane, on the VALU only (no LDS
+// round trips): xor-1 and xor-2 inside quads and rotations by 4 and 8 inside rows of 16
+// lanes as DPP modifiers, then the row and half exchanges above.
+#define HEART_WAVE_REDUCE(T, v, OP)                                                      \
+  do {                                                                                   \
+    v = OP(v, __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(                          \
+                  0u, __builtin_bit_cast(uint32_t, v), 0xB1, 0xf, 0xf, false))); /* quad_perm [1,0,3,2] */ \
+    v = OP(v, __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(                          \
+                  0u, __builtin_bit_cast(uint32_t, v), 0x4E, 0xf, 0xf, false))); /* quad_perm [2,3,0,1] */ \
+    v = OP(v, __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(                          \
+                  0u, __builtin_bit_cast(uint32_t, v), 0x124, 0xf, 0xf, false))); /* row_ror:4 */ \
+    v = OP(v, __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(                          \
+                  0u, __builtin_bit_cast(uint32_t, v), 0x128, 0xf, 0xf, false))); /* row_ror:8 */ \
+    {                                                                                    \
+      uint32_t r0_, r1_;                                                                 \
+      swap_rows16(__builtin_bit_cast(uint32_t, v), r0_, r1_);                            \
+      v = OP(__builtin_bit_cast(T, r0_), __builtin_bit_cast(T, r1_));                    \
+    }                                                                                    \
+    {                                                                                    \
+      uint32_t r0_, r1_;                                                                 \
+      swap_halves32(__builtin_bit_cast(uint32_t, v), r0_, r1_);                          \
+      v = OP(__builtin_bit_cast(T, r0_), __builtin_bit_cast(T, r1_));                    \
+    }                                                                                    \
+  } while (0)
+#define HEART_OP_ADD(a, b) ((a) + (b))
+#define HEART_OP_FMAX(a, b) fmaxf((a), (b))
+
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+  HEART_WAVE_REDUCE(uint32_t, v, HEART_OP_ADD);
+  return v;
+}
+// Sum of per-lane masses below 2^40: two 32-bit reductions over the low 20 bits and the
+// rest (each stays below 2^32 for 64 lanes), recombined exactly.
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
+  uint32_t lo = (uint32_t)v & 0xfffffu, hi = (uint32_t)(v >> 20);
+  HEART_WAVE_REDUCE(uint32_t, lo, HEART_OP_ADD);
+  HEART_WAVE_REDUCE(uint32_t, hi, HEART_OP_ADD);
+  return ((unsigned long long)hi << 20) + lo;
+}
+__device__ __forceinline__ int wave_sum_i32(int v) { return (int)wave_sum_u32((uint32_t)v); }
+__device__ __forceinline__ float wave_max_f32(float v) {
+  HEART_WAVE_REDUCE(float, v, HEART_OP_FMAX);
+  return v;
+}
+__device__ __forceinline__ float wave_sum_f32(float v) {
+  HEART_WAVE_REDUCE(float, v, HEART_OP_ADD);
+  return v;
+}
+
 // launchers implemented per kernel file
 int launch_pool(const heart_shape &s, const void *q, const void *k, float *qblk, float *kblk,
                 float *qmean, float *kmean, hipStream_t st);

@@ -14,7 +14,8 @@
 //            is "every score above a threshold value v*, plus the lowest-index
 //            ties at v*", and v* is found by a 31-step bitwise search on the fp32
 //            bit pattern (positive floats order like their bit patterns), each
-//            step being one wave-wide integer reduction of the fixed-point mass.
+//            step being one wave-wide integer reduction of the fixed-point mass
+//            (DPP / lane-swap reductions on the VALU, no LDS traffic).
 //            All mass arithmetic is integer, so the result does not depend on the
 //            order of the reduction.  Rank positions for the ascending kept-index
 //            list come from wave ballots and population counts.
@@ -23,27 +24,6 @@
 namespace heart {
 
 constexpr int kRows = 8;  // query-block rows per workgroup
-
-__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
-#pragma unroll
-  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
-  return v;
-}
-__device__ __forceinline__ int wave_sum_i32(int v) {
-#pragma unroll
-  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
-  return v;
-}
-__device__ __forceinline__ float wave_max_f32(float v) {
-#pragma unroll
-  for (int s = 32; s >= 1; s >>= 1) v = fmaxf(v, __shfl_xor(v, s, 64));
-  return v;
-}
-__device__ __forceinline__ float wave_sum_f32(float v) {
-#pragma unroll
-  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
-  return v;
-}
 
 template <int CMAX>  // slots per lane; handles Nb <= 64 * CMAX
 __global__ __launch_bounds__(256) void mask_topp_kernel(
