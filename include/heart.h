@@ -114,7 +114,7 @@ int heart_drift(int B, int H, int D, const float *qmean, const float *kmean, flo
  *            row in its first kept_count entries (the rest is left untouched);
  *          kept_count int32 [B,H,Nb];
  *          scores_out fp32 [B,H,Nb,Nb] or NULL.
- * Supported: Nb <= HEART_MAX_NB; D a multiple of 4, D <= 256.
+ * Supported: Nb <= HEART_MAX_NB; D a multiple of 4, D <= 128.
  */
 int heart_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float *kblk,
                     const float *scores_in, const float *tau, const unsigned char *refresh,

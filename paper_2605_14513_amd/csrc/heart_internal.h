@@ -81,8 +81,12 @@ __device__ __forceinline__ void swap_halves32(uint32_t v, uint32_t &r0, uint32_t
       v = OP(__builtin_bit_cast(T, r0_), __builtin_bit_cast(T, r1_));                    \
     }                                                                                    \
   } while (0)
+// (functions, not expression macros: each argument -- a DPP read -- must be evaluated
+// exactly once and with all lanes active)
+__device__ __forceinline__ uint32_t heart_op_umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
 #define HEART_OP_ADD(a, b) ((a) + (b))
 #define HEART_OP_FMAX(a, b) fmaxf((a), (b))
+#define HEART_OP_UMAX(a, b) heart_op_umax((a), (b))
 
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
   HEART_WAVE_REDUCE(uint32_t, v, HEART_OP_ADD);

@@ -4,11 +4,12 @@
 // 1/sqrt(D) interaction scale from the appendix on query-key stability).
 //
 // One workgroup (4 wavefronts) owns R = 8 query-block rows of one head.
-//   Phase A  logits[r][j] = qblk_r . kblk_j / sqrt(D): lane <-> key-block column,
-//            all R rows per lane, fp64 fused multiply-add (on this chip fp64 FMA
-//            issues at the rate of unpacked fp32 FMA, and it takes the dot product
-//            out of the error budget of the scores).  The R query rows sit in LDS
-//            as fp64 and are read as wave-wide broadcasts.
+//   Phase A  logits[r][j] = qblk_r . kblk_j / sqrt(D): the key blocks stream through
+//            LDS in chunks of 32 columns (coalesced loads, next chunk in flight),
+//            one (row, column) dot product per lane and chunk in fp64 fused
+//            multiply-add (on this chip fp64 FMA issues at the rate of unpacked
+//            fp32 FMA, and it takes the dot product out of the error budget of the
+//            scores).  The R query rows sit in LDS as fp64.
 //   Phase B  row softmax, one wavefront per row, fp32 with the accurate expf.
 //   Phase C  top-p selection, one wavefront per row, without sorting: the kept set
 //            is "every score above a threshold value v*, plus the lowest-index
@@ -23,7 +24,9 @@
 
 namespace heart {
 
-constexpr int kRows = 8;  // query-block rows per workgroup
+constexpr int kRows = 8;       // query-block rows per workgroup
+constexpr int kCols = 32;      // key-block columns staged through LDS at a time (kRows * kCols = 256 lanes)
+constexpr int kMaxStage = 4;   // float4 per lane for one staged chunk at D = 128
 
 template <int CMAX>  // slots per lane; handles Nb <= 64 * CMAX
 __global__ __launch_bounds__(256) void mask_topp_kernel(
@@ -36,6 +39,7 @@ __global__ __launch_bounds__(256) void mask_topp_kernel(
   constexpr int NBP = 64 * CMAX;
   double *sQ = reinterpret_cast<double *>(smem_raw);                       // [kRows][D]
   float *sP = reinterpret_cast<float *>(smem_raw + (size_t)kRows * D * 8);  // [kRows][NBP]
+  float *sKt = sP + kRows * NBP;                                            // [kCols][D + 4]
 
   const int groups = (Nb + kRows - 1) / kRows;
   const long long bh = blockIdx.x / groups;
@@ -52,27 +56,54 @@ __global__ __launch_bounds__(256) void mask_topp_kernel(
       int i = i0 + r;
       sQ[e] = i < Nb ? (double)qblk[((size_t)bh * Nb + i) * D + d] : 0.0;
     }
-    __syncthreads();
-    const double inv_sqrt_d = 1.0 / sqrt((double)D);
-    for (int j = threadIdx.x; j < Nb; j += 256) {
-      double acc[kRows];
+    // K blocks travel through LDS in chunks of kCols columns with coalesced 16-byte
+    // loads (the next chunk is in flight in registers while this one is consumed);
+    // thread (r, c) = (t / kCols, t % kCols) then owns one (query row, key column) dot
+    // product per chunk.  Row stride D + 4 floats spreads the columns over the banks.
+    const int D4 = D / 4;                      // float4 per K row
+    const int per_thread = (kCols * D4 + 255) / 256;
+    const int SKT = D + 4;
+    const float4 *kg = reinterpret_cast<const float4 *>(kblk + (size_t)bh * Nb * D);
+    float4 stage[kMaxStage];
+    auto load_chunk = [&](int c0) {
 #pragma unroll
-      for (int r = 0; r < kRows; ++r) acc[r] = 0.0;
-      const float4 *kp = reinterpret_cast<const float4 *>(kblk + ((size_t)bh * Nb + j) * D);
-      for (int d4 = 0; d4 < D / 4; ++d4) {
-        float4 kv = kp[d4];
-        double k0 = kv.x, k1 = kv.y, k2 = kv.z, k3 = kv.w;
-#pragma unroll
-        for (int r = 0; r < kRows; ++r) {
-          const double *qr = sQ + r * D + d4 * 4;
-          acc[r] = fma(k0, qr[0], acc[r]);
-          acc[r] = fma(k1, qr[1], acc[r]);
-          acc[r] = fma(k2, qr[2], acc[r]);
-          acc[r] = fma(k3, qr[3], acc[r]);
-        }
+      for (int u = 0; u < kMaxStage; ++u) {
+        const int e = threadIdx.x + u * 256;
+        const int col = e / D4, d4 = e % D4;
+        stage[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (u < per_thread && col < kCols && c0 + col < Nb) stage[u] = kg[(size_t)(c0 + col) * D4 + d4];
       }
+    };
+    auto store_chunk = [&]() {
 #pragma unroll
-      for (int r = 0; r < kRows; ++r) sP[r * NBP + j] = (float)(acc[r] * inv_sqrt_d);
+      for (int u = 0; u < kMaxStage; ++u) {
+        const int e = threadIdx.x + u * 256;
+        const int col = e / D4, d4 = e % D4;
+        if (u < per_thread && col < kCols) *reinterpret_cast<float4 *>(sKt + col * SKT + d4 * 4) = stage[u];
+      }
+    };
+    const double inv_sqrt_d = 1.0 / sqrt((double)D);
+    const int c = threadIdx.x % kCols, r = threadIdx.x / kCols;
+    load_chunk(0);
+    for (int c0 = 0; c0 < Nb; c0 += kCols) {
+      __syncthreads();  // previous chunk consumed (first pass: sQ written)
+      store_chunk();
+      __syncthreads();
+      if (c0 + kCols < Nb) load_chunk(c0 + kCols);
+      // four independent fp64 chains (a single one would be bound by FMA latency)
+      double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+      const float *kr = sKt + c * SKT;
+      const double *qr = sQ + r * D;
+#pragma unroll 4
+      for (int d4 = 0; d4 < D4; ++d4) {
+        const float4 kv = *reinterpret_cast<const float4 *>(kr + d4 * 4);
+        a0 = fma((double)kv.x, qr[d4 * 4 + 0], a0);
+        a1 = fma((double)kv.y, qr[d4 * 4 + 1], a1);
+        a2 = fma((double)kv.z, qr[d4 * 4 + 2], a2);
+        a3 = fma((double)kv.w, qr[d4 * 4 + 3], a3);
+      }
+      const double acc = (a0 + a1) + (a2 + a3);
+      if (c0 + c < Nb) sP[r * NBP + c0 + c] = (float)(acc * inv_sqrt_d);
     }
     __syncthreads();
   }
@@ -140,14 +171,35 @@ __global__ __launch_bounds__(256) void mask_topp_kernel(
       const unsigned long long T =
           tau_h > 0.f ? (unsigned long long)floorf(tau_h * 16777216.0f) : 0ull;
       const unsigned long long need = (T * U + 16777215ull) >> 24;
-      uint32_t v = 0;
-      for (int bit = 30; bit >= 0; --bit) {
+      // v* = largest bit pattern v with mass(scores >= v) >= need, built from the top
+      // bit down.  Invariant: mass(>= v) >= need > mass(>= v + 2^(bit+1)); the scores in
+      // [v, v + 2^(bit+1)) are undecided.  As soon as a single score is undecided it IS
+      // v* (keeping it reaches the mass, dropping it does not), so the loop stops early:
+      // typically after about a dozen steps instead of 31.  need == 0 keeps nothing here.
+      uint32_t v = need == 0 ? 0x7fffffffu : 0u;
+      for (int bit = 30; bit >= 0 && need != 0; --bit) {
         const uint32_t cand = v | (1u << bit);
         unsigned long long s = 0;
 #pragma unroll
         for (int c = 0; c < CMAX; ++c) s += e[c] >= cand ? u[c] : 0u;
         s = wave_sum_u64(s);
         if (s >= need) v = cand;
+        // undecided scores: [v, v + 2^bit) after this step (wave ballots, scalar counts)
+        const uint32_t top = v + (1u << bit);  // exclusive; bit patterns stay below 2^31
+        int n_und = 0;
+        uint32_t und = 0;
+#pragma unroll
+        for (int c = 0; c < CMAX; ++c) {
+          const bool in = e[c] >= v && e[c] < top;
+          n_und += __popcll(__ballot(in));
+          und = in ? e[c] : und;
+        }
+        if (n_und == 1) {
+          uint32_t x = und;  // the one lane that holds it has und != 0 unless it is 0
+          HEART_WAVE_REDUCE(uint32_t, x, HEART_OP_UMAX);
+          v = x > v ? x : v;
+          break;
+        }
       }
       unsigned long long s_gt = 0;
       int n_gt = 0;
@@ -217,7 +269,9 @@ static int launch_cmax(int B, int H, int Nb, int D, const float *qblk, const flo
                        int n_always_kv, int n_dense_q, int min_keep, unsigned char *mask,
                        int *kept_idx, int *kept_count, float *scores_out, hipStream_t st) {
   int groups = (Nb + kRows - 1) / kRows;
-  size_t lds = scores_in ? 0 : (size_t)kRows * D * 8 + (size_t)kRows * 64 * CMAX * 4;
+  size_t lds = scores_in ? 0
+                         : (size_t)kRows * D * 8 + (size_t)kRows * 64 * CMAX * 4 +
+                               (size_t)kCols * (D + 4) * 4;
   long long nwg = (long long)B * H * groups;
   hipLaunchKernelGGL(mask_topp_kernel<CMAX>, dim3((unsigned)nwg), dim3(256), lds, st, H, Nb, D,
                      qblk, kblk, scores_in, tau, refresh, n_always_kv, n_dense_q, min_keep, mask,

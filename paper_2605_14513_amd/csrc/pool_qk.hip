@@ -11,12 +11,14 @@
 //   rows in fp32 in row order, the 256/(D/8) row groups are combined through LDS
 //   in a fixed order (no atomics: results are reproducible), and the block mean is
 //   written once.
-// Kernel 2 (pool_token_mean): one workgroup per (tensor, b, h) sums
+// Kernel 2 (pool_token_mean): one workgroup of 1024 lanes per (tensor, b, h) sums
 //   block_mean * n_block over the blocks in fp64 in a fixed order and divides by N.
 //   (mean of block means would be wrong when the last block is short.)
 #include "heart_internal.h"
 
 namespace heart {
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 template <int D>
 __global__ __launch_bounds__(256) void pool_blocks_kernel(
@@ -51,7 +53,12 @@ __global__ __launch_bounds__(256) void pool_blocks_kernel(
   for (int p = 0; p < MAXP; ++p) {
     int r = row0 + p * RPP;
     v[p] = make_uint4(0u, 0u, 0u, 0u);
-    if (r < nrows) v[p] = *reinterpret_cast<const uint4 *>(base + (long long)(n0 + r) * sn + lane_col);
+    if (r < nrows) {
+      // streaming read: every byte is used once by this kernel
+      const u32x4 t = __builtin_nontemporal_load(
+          reinterpret_cast<const u32x4 *>(base + (long long)(n0 + r) * sn + lane_col));
+      v[p] = make_uint4(t.x, t.y, t.z, t.w);
+    }
   }
   float acc[8];
 #pragma unroll
@@ -78,17 +85,18 @@ __global__ __launch_bounds__(256) void pool_blocks_kernel(
   }
 }
 
-// One workgroup (256 lanes) per (tensor, b, h).  Lanes are arranged as D/4 column
-// groups (float4 each) times 256/(D/4) block-slices; each slice adds its blocks in
-// increasing block order in fp64, slices are combined in slice order.
+// One workgroup (1024 lanes) per (tensor, b, h).  Lanes are arranged as D/4 column
+// groups (float4 each) times 1024/(D/4) block-slices; each slice adds its blocks in
+// increasing block order in fp64 (loads of a slice are independent and issued
+// several at a time), slices are combined in slice order.
 template <int D>
-__global__ __launch_bounds__(256) void pool_token_mean_kernel(const float *__restrict__ qblk,
-                                                              const float *__restrict__ kblk,
-                                                              int N, int block, int Nb,
-                                                              float *__restrict__ qmean,
-                                                              float *__restrict__ kmean) {
+__global__ __launch_bounds__(1024) void pool_token_mean_kernel(const float *__restrict__ qblk,
+                                                               const float *__restrict__ kblk,
+                                                               int N, int block, int Nb,
+                                                               float *__restrict__ qmean,
+                                                               float *__restrict__ kmean) {
   constexpr int CG = D / 4;       // column groups
-  constexpr int SL = 256 / CG;    // slices over the blocks
+  constexpr int SL = 1024 / CG;   // slices over the blocks
   __shared__ double part[SL][D];
   int which = blockIdx.x & 1;
   long long bh = blockIdx.x >> 1;
@@ -98,6 +106,7 @@ __global__ __launch_bounds__(256) void pool_token_mean_kernel(const float *__res
   int per = (Nb + SL - 1) / SL;
   int i0 = sl * per, i1 = min(Nb, i0 + per);
   double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+#pragma unroll 8
   for (int i = i0; i < i1; ++i) {
     float4 m = *reinterpret_cast<const float4 *>(src + (size_t)i * D + cg * 4);
     double n = (double)min(block, N - i * block);
@@ -125,21 +134,21 @@ int launch_pool(const heart_shape &s, const void *q, const void *k, float *qblk,
   long long nwg = 2LL * s.B * s.H * Nb;
   if (nwg > 0x7fffffffLL) return fail(HEART_EUNSUPPORTED, "heart_pool_qk: grid too large");
   const uint16_t *qp = (const uint16_t *)q, *kp = (const uint16_t *)k;
-  dim3 grid((unsigned)nwg), blk(256);
+  dim3 grid((unsigned)nwg), blk(256), blk2(1024);
   dim3 grid2((unsigned)(2 * s.B * s.H));
   if (s.D == 128) {
     hipLaunchKernelGGL(pool_blocks_kernel<128>, grid, blk, 0, st, qp, kp, s.q_stride[0],
                        s.q_stride[1], s.q_stride[2], s.k_stride[0], s.k_stride[1], s.k_stride[2],
                        s.H, s.N, s.block, Nb, qblk, kblk);
     if (int rc = check_launch("pool_blocks_kernel")) return rc;
-    hipLaunchKernelGGL(pool_token_mean_kernel<128>, grid2, blk, 0, st, qblk, kblk, s.N, s.block,
+    hipLaunchKernelGGL(pool_token_mean_kernel<128>, grid2, blk2, 0, st, qblk, kblk, s.N, s.block,
                        Nb, qmean, kmean);
   } else {
     hipLaunchKernelGGL(pool_blocks_kernel<64>, grid, blk, 0, st, qp, kp, s.q_stride[0],
                        s.q_stride[1], s.q_stride[2], s.k_stride[0], s.k_stride[1], s.k_stride[2],
                        s.H, s.N, s.block, Nb, qblk, kblk);
     if (int rc = check_launch("pool_blocks_kernel")) return rc;
-    hipLaunchKernelGGL(pool_token_mean_kernel<64>, grid2, blk, 0, st, qblk, kblk, s.N, s.block,
+    hipLaunchKernelGGL(pool_token_mean_kernel<64>, grid2, blk2, 0, st, qblk, kblk, s.N, s.block,
                        Nb, qmean, kmean);
   }
   return check_launch("pool_token_mean_kernel");
