@@ -25,6 +25,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "block_sparse_attn_wan14b_480p_hbm_traffic.json")
 PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0           # MI355X HBM3E
 
@@ -37,6 +38,9 @@ def parse_args():
     ap.add_argument("--workload", default="wan14b_480p")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gate", default="0.4,0.8", help="layer gate lo,hi (0,1 disables)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 1 GiB device copies (reference for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     return ap.parse_args()
 
 
@@ -52,6 +56,19 @@ def kept_flops(kept_idx, kept_count, N, block, D):
     nj = n[kept_idx.clamp(0, Nb - 1).long()] * valid
     per_row = nj.sum(-1) * n[None, None, :]
     return float(4.0 * D * per_row.sum().item())
+
+
+def attn_traffic(workload):
+    """HBM bytes per launch of the attention kernel from the committed rocprofv3 --pmc
+    summary (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size), or None."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            t = json.load(f)
+        if t.get("workload") != workload:
+            return None
+        return float(t["fetch_bytes_per_launch"]) + float(t["write_bytes_per_launch"])
+    except (OSError, ValueError, KeyError):
+        return None
 
 
 def cpu_baseline(name, tau_all, delta_all):
@@ -78,7 +95,7 @@ def cpu_baseline(name, tau_all, delta_all):
     t_mask = time.perf_counter() - t0
     # attention on a sample of query blocks per head, sized for roughly 10-20 s of CPU work
     rng = np.random.default_rng(0)
-    nq = min(30, cfg.Nb)
+    nq = min(128, cfg.Nb)
     qblocks = sorted(set([0, cfg.Nb - 1] + rng.choice(cfg.Nb, size=nq, replace=False).tolist()))
     t0 = time.perf_counter()
     oracle.attn(q, k, v, cfg.block, idx, cnt, qblocks=qblocks)
@@ -91,13 +108,15 @@ def cpu_baseline(name, tau_all, delta_all):
             for i in qblocks:
                 fl += 4.0 * cfg.D * n[i] * n[idx[b, h, i, :cnt[b, h, i]]].sum()
     return {
-        "value": fl / t_attn / 1e12,
+        # whole step like `value`: the sample's share of the pooling/drift/mask time is included
+        "value": fl / (t_attn + t_mask * len(qblocks) / cfg.Nb) / 1e12,
         "unit": "TFLOP/s",
         "cores": oracle.num_threads(),
         "kind": "oracle",
         "sample": (f"step 0 of {name}, heads {heads}: pool+drift+scores+top-p in full for these "
                    f"heads, sparse attention on query blocks {qblocks} of each; value = kept-block "
-                   f"attention FLOPs / oracle attention time"),
+                   f"attention FLOPs of the sample / (oracle attention time + the sampled share of "
+                   f"its pool/drift/mask time)"),
         "attn_seconds_on_sample": t_attn,
         "mask_refresh_us_per_step_extrapolated": t_mask * 1e6 * cfg.H / nh,
     }
@@ -178,7 +197,6 @@ def main():
 
     # ---- timed region: exactly K steps, HIP events on the launch stream around each call ----
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K)]
-    stats = []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for it in range(K):
@@ -241,7 +259,7 @@ def main():
             "peak": PEAK_BF16_MFMA_TFLOPS,
             "unit": "TFLOP/s",
             "frac": attn_tflops / PEAK_BF16_MFMA_TFLOPS,
-            "traffic": None,
+            "traffic": attn_traffic(args.workload),
         },
         "roofline_hbm_kernels": {
             "heart_pool_qk": {"bound": "hbm", "achieved": pool_bytes / (pool_ms * 1e-3) / 1e9,
@@ -252,6 +270,13 @@ def main():
                                 "frac": mask_bytes / (mask_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
         },
     }
+    if args.calibrate_copy:
+        src = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample", file=sys.stderr, flush=True)
         result["cpu_baseline"] = cpu_baseline(args.workload, g.tau, g.delta)

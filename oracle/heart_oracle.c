@@ -22,8 +22,7 @@
  *   oracle_attn       softmax attention restricted to kept key blocks
  *   oracle_dense_attn unblocked dense attention (brute force, for tests)
  *
- * Readings where the paper is silent are listed in the repository's design notes;
- * the ones that shape this file: ties rank lower key-block index first; "reaches"
+ * Readings where the paper is silent that shape this file: ties rank lower key-block index first; "reaches"
  * is >=; cumulative mass is an integer fixed point (floor(P * 2^30)) compared
  * against tau * total so the kept set does not depend on summation order;
  * tau >= 1 keeps every block; drift is summed (not averaged) over D.

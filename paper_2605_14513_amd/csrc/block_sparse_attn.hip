@@ -248,7 +248,6 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   //   barrier B before W: every wave has read V^T half 1; new sK / half 0 visible
   //   V^T half-1 stores in W; they are first read after the next barrier A
   constexpr int NSL = BLK / 32;           // slices per key block
-  constexpr int EPM = 16 / KS;            // softmax elements handled per S^T MFMA
   constexpr int NPV = 2 * DT;             // MFMAs of one slice's O^T update
   constexpr int STEP = KS + NPV;
   constexpr int G_A = (NSL - 2) * STEP + KS;       // stream position of barrier A: C(NSL-2)
