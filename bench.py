@@ -25,7 +25,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "block_sparse_attn_wan14b_480p_hbm_traffic.json")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "block_sparse_attn_wan14b_480p_hbm_traffic.txt")
 PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0           # MI355X HBM3E
 
@@ -62,8 +62,12 @@ def attn_traffic(workload):
     """HBM bytes per launch of the attention kernel from the committed rocprofv3 --pmc
     summary (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size), or None."""
     try:
+        t = {}
         with open(TRAFFIC_FILE) as f:
-            t = json.load(f)
+            for line in f:
+                if ":" in line and not line.startswith("#"):
+                    key, val = line.split(":", 1)
+                    t[key.strip()] = val.strip()
         if t.get("workload") != workload:
             return None
         return float(t["fetch_bytes_per_launch"]) + float(t["write_bytes_per_launch"])
@@ -173,6 +177,7 @@ def main():
     kidx = torch.zeros((B, H, Nb, Nb), dtype=torch.int32, device=dev)
     kcnt = torch.zeros((B, H, Nb), dtype=torch.int32, device=dev)
     out = torch.empty_like(steps_in[0][0])
+    attn_ws = torch.empty(heart.heart_attn_workspace_bytes(out, blk), dtype=torch.uint8, device=dev)
 
     def one_step(it, ev=None):
         s = it % S
@@ -187,7 +192,7 @@ def main():
         heart.heart_mask_topp(qblk, kblk, tau, refresh=refresh, n_always_kv_blocks=nt,
                               n_dense_q_blocks=nt, mask=mask, kept_idx=kidx, kept_count=kcnt)
         if ev: ev[3].record()
-        heart.heart_block_sparse_attn(q, k, v, blk, kidx, kcnt, out=out)
+        heart.heart_block_sparse_attn(q, k, v, blk, kidx, kcnt, out=out, workspace=attn_ws)
         if ev: ev[4].record()
 
     K, W = args.steps, args.warmup

@@ -9,7 +9,8 @@
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller (for instance the
  *     storage of PyTorch-ROCm tensors).  The library allocates nothing, keeps no
- *     state between calls, reads no environment variable.
+ *     state between calls, reads no environment variable; the one kernel that needs
+ *     scratch memory takes it as a workspace argument.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call
  *     only enqueues kernels on that stream and returns; it never synchronises.
  *   - Return value: HEART_OK (0) or a negative error code.  After an error
@@ -135,10 +136,20 @@ int heart_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float 
  * does not matter for the result up to rounding); scale <= 0 means 1/sqrt(D);
  * lse: fp32 [B,H,N] natural-log-sum-exp of the scaled logits over the kept keys,
  * or NULL.  A row with kept_count == 0 yields zeros (lse = -inf).
+ * workspace: device memory of at least heart_attn_workspace_bytes(shape) bytes, 16-byte
+ * aligned, or NULL.  With a workspace the call first builds a launch order in it
+ * (query blocks with the longest kept lists start first, which removes most of the
+ * idle tail when kept counts differ between rows); the results are the same with and
+ * without it.  The contents need not be preserved between calls; two calls that run
+ * concurrently must not share a workspace.
  */
 int heart_block_sparse_attn(const heart_shape *shape, const void *q_bf16, const void *k_bf16,
                             const void *v_bf16, const int *kept_idx, const int *kept_count,
-                            float scale, void *out_bf16, float *lse, void *stream);
+                            float scale, void *out_bf16, float *lse, void *workspace,
+                            size_t workspace_bytes, void *stream);
+
+/* Bytes of workspace heart_block_sparse_attn can use for `shape` (0 if shape is invalid). */
+size_t heart_attn_workspace_bytes(const heart_shape *shape);
 
 /* Thread-local message of the last error returned on this thread ("" if none). */
 const char *heart_last_error(void);

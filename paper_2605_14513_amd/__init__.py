@@ -5,6 +5,7 @@ kernels, and importing/calling it without the built library fails loudly."""
 from .binding import (  # noqa: F401
     HeartError,
     HeartShape,
+    heart_attn_workspace_bytes,
     heart_block_sparse_attn,
     heart_drift,
     heart_last_error,

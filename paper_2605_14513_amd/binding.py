@@ -57,7 +57,10 @@ def load_library() -> ctypes.CDLL:
     lib.heart_drift.argtypes = [ci, ci, ci, vp, vp, vp, vp, vp, vp, cf, cf, ci, vp, vp, vp]
     lib.heart_mask_topp.argtypes = [ci, ci, ci, ci, vp, vp, vp, vp, vp, ci, ci, ci, vp, vp, vp,
                                     vp, vp]
-    lib.heart_block_sparse_attn.argtypes = [sp, vp, vp, vp, vp, vp, cf, vp, vp, vp]
+    lib.heart_block_sparse_attn.argtypes = [sp, vp, vp, vp, vp, vp, cf, vp, vp, vp,
+                                            ctypes.c_size_t, vp]
+    lib.heart_attn_workspace_bytes.argtypes = [sp]
+    lib.heart_attn_workspace_bytes.restype = ctypes.c_size_t
     for f in (lib.heart_pool_qk, lib.heart_drift, lib.heart_mask_topp,
               lib.heart_block_sparse_attn, lib.heart_version):
         f.restype = ci
@@ -203,9 +206,17 @@ def heart_mask_topp(qblk, kblk, tau, refresh=None, scores_in=None, n_always_kv_b
     return mask, kept_idx, kept_count
 
 
+def heart_attn_workspace_bytes(q, block: int) -> int:
+    """Bytes of workspace heart_block_sparse_attn can use for tensors shaped like q."""
+    return int(load_library().heart_attn_workspace_bytes(ctypes.byref(make_shape(q, q, block))))
+
+
 def heart_block_sparse_attn(q, k, v, block: int, kept_idx, kept_count, scale: float = 0.0,
-                            out=None, lse=None):
-    """Block-sparse attention over the kept key blocks; returns bf16 out like q."""
+                            out=None, lse=None, workspace="auto"):
+    """Block-sparse attention over the kept key blocks; returns bf16 out like q.
+
+    workspace: a uint8/int32 GPU tensor of at least heart_attn_workspace_bytes, None (natural
+    launch order), or "auto" (a fresh tensor from torch's allocator)."""
     lib = load_library()
     if q.shape != k.shape or q.shape != v.shape:
         raise ValueError("q, k, v must have the same shape")
@@ -218,12 +229,22 @@ def heart_block_sparse_attn(q, k, v, block: int, kept_idx, kept_count, scale: fl
     if lse is not None and tuple(lse.shape) != (B, H, N):
         raise ValueError("lse must be [B,H,N]")
     shape = make_shape(q, k, block, v, out)
+    if isinstance(workspace, str):
+        if workspace != "auto":
+            raise ValueError("workspace must be a tensor, None or 'auto'")
+        workspace = torch.empty(int(lib.heart_attn_workspace_bytes(ctypes.byref(shape))),
+                                dtype=torch.uint8, device=q.device)
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        if not workspace.is_cuda or not workspace.is_contiguous():
+            raise ValueError("workspace must be a contiguous GPU tensor")
+        ws_ptr, ws_bytes = ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
     rc = lib.heart_block_sparse_attn(ctypes.byref(shape), _dev(q, torch.bfloat16, "q", False),
                                      _dev(k, torch.bfloat16, "k", False),
                                      _dev(v, torch.bfloat16, "v", False),
                                      _dev(kept_idx, torch.int32, "kept_idx"),
                                      _dev(kept_count, torch.int32, "kept_count"), float(scale),
                                      _dev(out, torch.bfloat16, "out", False),
-                                     _dev(lse, torch.float32, "lse"), _stream())
+                                     _dev(lse, torch.float32, "lse"), ws_ptr, ws_bytes, _stream())
     _check("heart_block_sparse_attn", rc)
     return out

@@ -35,9 +35,13 @@
 // for the descriptor and read as zero, with no branch and no address clamping.
 //
 // Workgroup ids are remapped (they are dealt round-robin to the 8 XCDs, each with its
-// own L2) so that an XCD works on a contiguous eighth of the query blocks of every
-// head: balanced across XCDs, and neighbouring query blocks share their kept K/V
-// blocks through that XCD's L2.
+// own L2).  With a work-order list (attn_order_kernel, when the caller passes a
+// workspace) the query blocks are launched longest first: kept counts range from 1 to
+// Nb per row, and a long row that starts late would otherwise leave most of the chip
+// idle at the end.  The order is a stable counting sort on 32 count classes, so rows of
+// a class keep their natural order (same head, neighbouring query blocks, which share
+// kept K/V blocks), and runs of 8 consecutive list entries go to the same XCD.  Without
+// a list an XCD works on a contiguous eighth of the query blocks of every head.
 #include "heart_internal.h"
 
 namespace heart {
@@ -74,6 +78,69 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t head_rsrc(const uint16_t *base
 }
 
 constexpr int kNumXcd = 8;
+constexpr int kOrderRun = 8;      // consecutive work-list entries that go to one XCD
+constexpr int kOrderClasses = 32; // count classes of the work-order sort
+
+// Work order for the attention launch: a permutation of the n = B*H*Nb (head, query
+// block) items, longest kept list first.  Stable counting sort by count class
+// (class 0 = the longest rows) in one workgroup: thread t owns a contiguous segment of
+// the items and one column of the class histogram, so that items of a class keep
+// their natural order.
+__global__ __launch_bounds__(256) void attn_order_kernel(const int *__restrict__ kept_count, int n,
+                                                         int Nb, int *__restrict__ order) {
+  __shared__ int hist[kOrderClasses][256];
+  __shared__ int scan[256];
+  const int t = threadIdx.x;
+  const int per = (n + 255) / 256;
+  const int i0 = min(n, t * per), i1 = min(n, i0 + per);
+  auto cls = [&](int c) -> int {
+    c = min(max(c, 0), Nb);
+    return (kOrderClasses - 1) - (int)(((long long)c * (kOrderClasses - 1)) / Nb);
+  };
+#pragma unroll
+  for (int b = 0; b < kOrderClasses; ++b) hist[b][t] = 0;
+  for (int i = i0; i < i1; i += 8) {
+    int c[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) c[e] = i + e < i1 ? kept_count[i + e] : 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (i + e < i1) hist[cls(c[e])][t] += 1;
+  }
+  __syncthreads();
+  // exclusive scan over the histogram flattened class-major (index = class * 256 + thread)
+  int *flat = &hist[0][0];
+  int sum = 0;
+  for (int j = 0; j < kOrderClasses; ++j) sum += flat[t * kOrderClasses + j];
+  scan[t] = sum;
+  __syncthreads();
+  for (int d = 1; d < 256; d <<= 1) {
+    const int add = t >= d ? scan[t - d] : 0;
+    __syncthreads();
+    scan[t] += add;
+    __syncthreads();
+  }
+  int run = scan[t] - sum;
+  for (int j = 0; j < kOrderClasses; ++j) {
+    const int x = flat[t * kOrderClasses + j];
+    flat[t * kOrderClasses + j] = run;
+    run += x;
+  }
+  __syncthreads();
+  for (int i = i0; i < i1; i += 8) {
+    int c[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) c[e] = i + e < i1 ? kept_count[i + e] : 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (i + e < i1) {
+        const int b = cls(c[e]);
+        const int pos = hist[b][t];
+        hist[b][t] = pos + 1;
+        order[pos] = i + e;
+      }
+  }
+}
 #ifndef HEART_ATTN_PF
 #define HEART_ATTN_PF 4
 #endif
@@ -88,7 +155,7 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
     long long qsn, long long ksb, long long ksh, long long ksn, long long vsb, long long vsh,
     long long vsn, long long osb, long long osh, long long osn, int H, int BH, int N, int Nb,
     const int *__restrict__ kept_idx, const int *__restrict__ kept_count, float scale_log2e,
-    float *__restrict__ lse) {
+    float *__restrict__ lse, const int *__restrict__ order, int n_items) {
   constexpr int NT = BLK * 2;            // threads
   constexpr int DT = D / 32;             // 32-wide d tiles of the output
   constexpr int KS = D / 16;             // k-steps of the first contraction
@@ -112,7 +179,17 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   // unbalanced), neighbouring query blocks -- whose kept key blocks overlap -- share
   // an L2, and at any time only one or two heads' K/V are live in the memory-side cache.
   int bh, qb;
-  {
+  if (order) {
+    // list position: runs of kOrderRun consecutive entries per XCD, XCDs interleaved
+    const int xcd = (int)(blockIdx.x % kNumXcd);
+    const long long slot = blockIdx.x / kNumXcd;
+    const long long pos =
+        (slot / kOrderRun) * (kNumXcd * kOrderRun) + xcd * kOrderRun + slot % kOrderRun;
+    if (pos >= n_items) return;  // padding (whole workgroup, before any barrier)
+    const int item = min(max(order[pos], 0), n_items - 1);
+    bh = item / Nb;
+    qb = item % Nb;
+  } else {
     const int per = (Nb + kNumXcd - 1) / kNumXcd;  // query blocks per XCD and head
     const int xcd = (int)(blockIdx.x % kNumXcd);
     const long long slot = blockIdx.x / kNumXcd;
@@ -520,7 +597,7 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
 template <int D, int BLK>
 static int launch_attn_t(const heart_shape &s, const void *q, const void *k, const void *v,
                          const int *kept_idx, const int *kept_count, float scale, void *out,
-                         float *lse, hipStream_t st) {
+                         float *lse, int *order, hipStream_t st) {
   const int Nb = (s.N + BLK - 1) / BLK;
   const int BH = s.B * s.H;
   const size_t lds = ((size_t)BLK * (D + 8) + (size_t)D * (BLK + 8)) * 2;
@@ -536,20 +613,28 @@ static int launch_attn_t(const heart_shape &s, const void *q, const void *k, con
   }
   const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
   const float scale_log2e = sc * 1.4426950408889634f;
-  const long long grid = (long long)BH * ((Nb + kNumXcd - 1) / kNumXcd) * kNumXcd;
+  const long long n_items = (long long)BH * Nb;
+  constexpr long long kGroup = kNumXcd * kOrderRun;
+  const long long grid = order ? (n_items + kGroup - 1) / kGroup * kGroup
+                               : (long long)BH * ((Nb + kNumXcd - 1) / kNumXcd) * kNumXcd;
   if (grid > 0x7fffffffLL) return fail(HEART_EUNSUPPORTED, "heart_block_sparse_attn: grid too large");
+  if (order) {
+    hipLaunchKernelGGL(attn_order_kernel, dim3(1), dim3(256), 0, st, kept_count, (int)n_items, Nb,
+                       order);
+    if (int rc = check_launch("attn_order_kernel")) return rc;
+  }
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(BLK * 2), lds, st,
                      (const uint16_t *)q, (const uint16_t *)k, (const uint16_t *)v,
                      (uint16_t *)out, s.q_stride[0], s.q_stride[1], s.q_stride[2], s.k_stride[0],
                      s.k_stride[1], s.k_stride[2], s.v_stride[0], s.v_stride[1], s.v_stride[2],
                      s.o_stride[0], s.o_stride[1], s.o_stride[2], s.H, BH, s.N, Nb, kept_idx,
-                     kept_count, scale_log2e, lse);
+                     kept_count, scale_log2e, lse, (const int *)order, (int)n_items);
   return check_launch("attn_kernel");
 }
 
 int launch_attn(const heart_shape &s, const void *q, const void *k, const void *v,
                 const int *kept_idx, const int *kept_count, float scale, void *out, float *lse,
-                hipStream_t st) {
+                int *order, hipStream_t st) {
   // the kernel addresses one head's rows through 32-bit buffer offsets
   const long long lim = 0xffffffffLL;
   const long long rows = (long long)s.N + 2 * s.block;  // staging may address a few rows past N
@@ -559,11 +644,11 @@ int launch_attn(const heart_shape &s, const void *q, const void *k, const void *
                 "heart_block_sparse_attn: (N + 2*block) * token stride * 2 bytes must stay "
                 "below 4 GiB");
   if (s.D == 128 && s.block == 128)
-    return launch_attn_t<128, 128>(s, q, k, v, kept_idx, kept_count, scale, out, lse, st);
+    return launch_attn_t<128, 128>(s, q, k, v, kept_idx, kept_count, scale, out, lse, order, st);
   if (s.D == 64 && s.block == 128)
-    return launch_attn_t<64, 128>(s, q, k, v, kept_idx, kept_count, scale, out, lse, st);
+    return launch_attn_t<64, 128>(s, q, k, v, kept_idx, kept_count, scale, out, lse, order, st);
   if (s.D == 64 && s.block == 64)
-    return launch_attn_t<64, 64>(s, q, k, v, kept_idx, kept_count, scale, out, lse, st);
+    return launch_attn_t<64, 64>(s, q, k, v, kept_idx, kept_count, scale, out, lse, order, st);
   return fail(HEART_EUNSUPPORTED, "heart_block_sparse_attn: unsupported (D, block) = (%d, %d)",
               s.D, s.block);
 }

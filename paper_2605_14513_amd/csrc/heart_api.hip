@@ -118,7 +118,8 @@ int heart_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float 
 
 int heart_block_sparse_attn(const heart_shape *shape, const void *q, const void *k,
                             const void *v, const int *kept_idx, const int *kept_count,
-                            float scale, void *out, float *lse, void *stream) {
+                            float scale, void *out, float *lse, void *workspace,
+                            size_t workspace_bytes, void *stream) {
   clear_error();
   if (int rc = check_shape(shape, "heart_block_sparse_attn")) return rc;
   if (!q || !k || !v || !kept_idx || !kept_count || !out)
@@ -135,8 +136,21 @@ int heart_block_sparse_attn(const heart_shape *shape, const void *q, const void 
     return fail(HEART_EUNSUPPORTED,
                 "heart_block_sparse_attn: supported (D, block) pairs are (128,128), (64,128), "
                 "(64,64)");
-  return launch_attn(*shape, q, k, v, kept_idx, kept_count, scale, out, lse,
+  if (workspace) {
+    if (!aligned16(workspace))
+      return fail(HEART_EUNSUPPORTED, "heart_block_sparse_attn: workspace must be 16-byte aligned");
+    if (workspace_bytes < heart_attn_workspace_bytes(shape))
+      return fail(HEART_EINVAL, "heart_block_sparse_attn: workspace of %zu bytes, need %zu",
+                  workspace_bytes, heart_attn_workspace_bytes(shape));
+  }
+  return launch_attn(*shape, q, k, v, kept_idx, kept_count, scale, out, lse, (int *)workspace,
                      (hipStream_t)stream);
+}
+
+size_t heart_attn_workspace_bytes(const heart_shape *s) {
+  if (!s || s->B <= 0 || s->H <= 0 || s->N <= 0 || s->block <= 0) return 0;
+  const size_t nb = ((size_t)s->N + s->block - 1) / s->block;
+  return (size_t)s->B * s->H * nb * sizeof(int);
 }
 
 }  // extern "C"

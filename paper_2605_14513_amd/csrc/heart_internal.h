@@ -123,6 +123,6 @@ int launch_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float
                      int *kept_idx, int *kept_count, float *scores_out, hipStream_t st);
 int launch_attn(const heart_shape &s, const void *q, const void *k, const void *v,
                 const int *kept_idx, const int *kept_count, float scale, void *out, float *lse,
-                hipStream_t st);
+                int *order, hipStream_t st);
 
 }  // namespace heart

@@ -322,6 +322,39 @@ def test_attn_strided_layout_unsorted_lists_and_empty_rows(heart):
     assert err <= ATTN_ATOL, f"max abs err {err:.4f}"
 
 
+def test_attn_launch_order_is_a_stable_longest_first_permutation(heart):
+    # the workspace receives the launch order: a permutation of all (head, query block)
+    # items, sorted by count class (longest first), natural order inside a class; the
+    # output bits do not depend on the order
+    g, st = case("small_ragged")
+    cfg = g.cfg
+    rng = np.random.default_rng(9)
+    Nb = cfg.Nb
+    cnt = rng.integers(0, Nb + 1, size=(cfg.B, cfg.H, Nb)).astype(np.int32)
+    idx = np.zeros((cfg.B, cfg.H, Nb, Nb), np.int32)
+    for b in range(cfg.B):
+        for h in range(cfg.H):
+            for i in range(Nb):
+                idx[b, h, i, :cnt[b, h, i]] = np.sort(rng.permutation(Nb)[:cnt[b, h, i]])
+    q, k, v = gpu(st.q), gpu(st.k), gpu(st.v)
+    n = cfg.B * cfg.H * Nb
+    assert heart.heart_attn_workspace_bytes(q, cfg.block) == 4 * n
+    ws = torch.full((n + 3,), -7, dtype=torch.int32, device="cuda")
+    out_ordered = heart.heart_block_sparse_attn(q, k, v, cfg.block, np_gpu(idx), np_gpu(cnt), workspace=ws)
+    out_natural = heart.heart_block_sparse_attn(q, k, v, cfg.block, np_gpu(idx), np_gpu(cnt), workspace=None)
+    torch.cuda.synchronize()
+    order = ws.cpu().numpy()
+    assert (order[n:] == -7).all()  # nothing written past the stated size
+    order = order[:n]
+    assert np.array_equal(np.sort(order), np.arange(n))
+    classes = 31 - (cnt.reshape(-1).astype(np.int64) * 31) // Nb
+    want = np.argsort(classes, kind="stable")
+    assert np.array_equal(order, want)
+    assert torch.equal(out_ordered, out_natural)
+    with pytest.raises(heart.HeartError):
+        heart.heart_block_sparse_attn(q, k, v, cfg.block, np_gpu(idx), np_gpu(cnt), workspace=ws[:n - 1])
+
+
 # ------------------------------------------------------------------------------ P6
 @pytest.mark.parametrize("name", ["tiny", "small_ragged", "small_text"])
 def test_chained_steps_match_oracle(heart, name):
