@@ -54,6 +54,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 // first-class values, so staging arrays of them always live in registers.
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 
 union Frag8 {
   u32x4_t u;
@@ -66,18 +67,24 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, b);
 }
 
-// registers that carry one thread's share of a K or V tile from global memory to LDS
-template <int n>
-struct Stage {
-  u32x4_t r[n];
-};
-
 // buffer descriptor over one head's rows: offsets >= bytes read as zero
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t head_rsrc(const uint16_t *base, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(base), 0, (int)bytes, 0x00020000);
 }
 
+// the same descriptor as four words in scalar registers, for hand-written buffer instructions
+__device__ __forceinline__ u32x4_t head_rsrc_words(const uint16_t *base, uint32_t bytes) {
+  const uint64_t a = reinterpret_cast<uint64_t>(base);
+  u32x4_t r;
+  r.x = __builtin_amdgcn_readfirstlane((uint32_t)a);
+  r.y = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32) & 0xffffu);
+  r.z = __builtin_amdgcn_readfirstlane(bytes);
+  r.w = 0x00020000u;
+  return r;
+}
+
 constexpr int kNumXcd = 8;
+constexpr int kStageRows = 64;    // key rows per K / V stage buffer (two 32-key slices)
 constexpr int kOrderRun = 8;      // consecutive work-list entries that go to one XCD
 constexpr int kOrderClasses = 32; // count classes of the work-order sort
 
@@ -157,27 +164,25 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
     const int *__restrict__ kept_idx, const int *__restrict__ kept_count, float scale_log2e,
     float *__restrict__ lse, const int *__restrict__ order, int n_items) {
   constexpr int NT = BLK * 2;            // threads
+  constexpr int NW = NT / 64;            // wavefronts
   constexpr int DT = D / 32;             // 32-wide d tiles of the output
   constexpr int KS = D / 16;             // k-steps of the first contraction
-  constexpr int SK = D + 8;              // LDS row stride of the K tile (elements)
-  constexpr int SV = BLK + 8;            // LDS row stride of the V^T tile (elements)
   constexpr int CPR = D / 8;             // 16-byte chunks per token row
-  constexpr int KCH = (BLK * CPR) / NT;  // K chunks per thread
-  constexpr int K_R_STEP = NT / CPR;     // rows between a thread's K chunks
-  constexpr int VIT = D / 64;            // V sub-tiles (4 keys x 8 d) per thread
-  constexpr int V_KG_STEP = 8 * ((NT / 32) / (D / 32));  // key groups between them
+  constexpr int ROWB = D * 2;            // bytes of a token row in LDS (no padding)
+  constexpr int RPB = 16 / CPR;          // rows per 256 bytes (one pass over the 64 banks)
+  constexpr int TILE_B = kStageRows * ROWB;  // bytes of one K or V stage buffer
+  constexpr int RPI = 64 / CPR;          // rows one LDS-direct load instruction covers
+  constexpr int IPW = kStageRows / RPI / NW;  // such instructions per wavefront and tile
+  constexpr int NSL = BLK / 32;          // 32-key slices per key block
+  constexpr int SO = D + 8;              // LDS row stride of the output staging (elements)
   constexpr float kRescaleSlack = 8.f;   // log2 units the running reference may lag the max
+  static_assert(NW % 2 == 0 && IPW >= 1 && (NSL == 2 || NSL == 4), "tile layout");
 
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  uint16_t *sK = reinterpret_cast<uint16_t *>(smem_raw);  // [BLK][SK]; reused for the output
-  uint16_t *sVT = sK + BLK * SK;                           // [D][SV]
+  // LDS: [K stage 0][K stage 1][V stage 0][V stage 1], reused for the output at the end
+  extern __shared__ __align__(1024) unsigned char smem[];
+  const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)smem;
 
   // ---- workgroup id -> (head, query block), XCD-aware ------------------------------
-  // Workgroup ids are dealt round-robin to the 8 XCDs.  XCD x takes the x-th eighth
-  // of the query blocks of EVERY head, heads in order: all XCDs then carry the same
-  // mix of heads (per-head density differs a lot, so whole heads per XCD would be
-  // unbalanced), neighbouring query blocks -- whose kept key blocks overlap -- share
-  // an L2, and at any time only one or two heads' K/V are live in the memory-side cache.
   int bh, qb;
   if (order) {
     // list position: runs of kOrderRun consecutive entries per XCD, XCDs interleaved
@@ -199,61 +204,76 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   }
   const int b = bh / H, h = bh % H;
   const int t = threadIdx.x;
-  const int lane = t & 63, wave = t >> 6;
+  const int lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int l32 = lane & 31, hf = lane >> 5;
 
   const __amdgpu_buffer_rsrc_t q_rs = head_rsrc(q + b * qsb + h * qsh, (uint32_t)(N * qsn * 2));
-  const __amdgpu_buffer_rsrc_t k_rs = head_rsrc(k + b * ksb + h * ksh, (uint32_t)(N * ksn * 2));
-  const __amdgpu_buffer_rsrc_t v_rs = head_rsrc(v + b * vsb + h * vsh, (uint32_t)(N * vsn * 2));
+  const u32x4_t k_rs = head_rsrc_words(k + b * ksb + h * ksh, (uint32_t)(N * ksn * 2));
+  const u32x4_t v_rs = head_rsrc_words(v + b * vsb + h * vsh, (uint32_t)(N * vsn * 2));
   const uint32_t k_row_bytes = (uint32_t)ksn * 2u, v_row_bytes = (uint32_t)vsn * 2u;
 
-  // K staging: chunk `it` of this thread is row k_r0 + it * K_R_STEP, 16-byte column k_c
-  const int k_r0 = t / CPR, k_c = (t % CPR) * 8;
-  const uint32_t k_off0 = (uint32_t)k_r0 * k_row_bytes + (uint32_t)k_c * 2u;
-  // V staging: sub-tile `it` is d-group v_dg (8 d), key group v_kg0 + it * V_KG_STEP (4 keys);
-  // lanes of a half-wave cover 4 d-groups x 8 key groups
-  const int v_dg = (t & 3) + 4 * ((t >> 5) % (D / 32));
-  const int v_kg0 = ((t & 31) >> 2) + 8 * ((t >> 5) / (D / 32));
-  const uint32_t v_off0 = (uint32_t)(v_kg0 * 4) * v_row_bytes + (uint32_t)v_dg * 16u;
-
-  // Staging is written per operation so that the loop can issue the loads and LDS
-  // stores one at a time in the shadow of MFMAs instead of in bursts after a barrier.
-  // K: chunk `it` (0 .. KCH-1) of this thread.
-  auto load_k1 = [&](Stage<KCH> &st, int it, int kv0) {
-    st.r[it] = __builtin_amdgcn_raw_buffer_load_b128(
-        k_rs, k_off0 + (uint32_t)(kv0 + it * K_R_STEP) * k_row_bytes, 0, 0);
+  // ---- per-lane constants of the LDS layout ---------------------------------------------
+  // Chunk c (16 bytes) of tile row r is stored at chunk position c ^ f(r):
+  //   K: f(r) = (r / RPB) % CPR      -- the 16 rows a quarter-wave reads with one
+  //                                     ds_read_b128 (same chunk, consecutive rows) fall
+  //                                     into 16 distinct 4-bank groups
+  //   V: f(r) = 4 * ((r / RPB) % (CPR/4)) -- the 4 rows x 4 chunks that 32 lanes read with
+  //                                     one transposing read fall into distinct groups
+  // K fragment of k-step ks (A operand of S^T): row l32 of the slice, chunk 2 ks + hf.
+  uint32_t koff[KS];
+  {
+    const int fk = (l32 / RPB) % CPR;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) koff[ks] = (uint32_t)(l32 * ROWB + (((2 * ks + hf) ^ fk) * 16));
+  }
+  // V^T fragment (A operand of O^T += V^T P^T) through ds_read_b64_tr_b16: within 16 lanes,
+  // lane s supplies the address of 4 consecutive d of one key (key s/4, d chunk s%4) and
+  // lane i receives d = i of keys 0..3.  A fragment (8 keys) is two such reads: keys
+  // 16 s2 + 4 hf + 0..3 and 16 s2 + 8 + 4 hf + 0..3 of the slice, the order in which the
+  // accumulator of S^T holds them.
+  uint32_t voff[DT];
+  {
+    const int s = lane & 15, g16 = (lane >> 4) & 1;
+    const int rowv = 4 * hf + (s >> 2);
+    const int fv4 = (rowv / RPB) % (CPR / 4);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+      voff[dt] = (uint32_t)(rowv * ROWB + ((4 * (dt ^ fv4) + 2 * g16 + ((s & 3) >> 1)) * 16) +
+                            (s & 1) * 8);
+  }
+  // LDS-direct loads: one instruction moves 16 bytes per lane to 1 KB of consecutive LDS
+  // (RPI rows); lane l lands at chunk position l % CPR of row l / CPR and therefore fetches
+  // global chunk (l % CPR) ^ f(row).  Wavefront w issues instructions w*IPW .. w*IPW+IPW-1
+  // of a tile.  Rows past the end of the sequence are out of range for the descriptor and
+  // arrive as zeros.
+  uint32_t kdma[IPW], vdma;
+  {
+    const int drow = lane / CPR, dp = lane % CPR;
+#pragma unroll
+    for (int ii = 0; ii < IPW; ++ii) {
+      const int r = (wave * IPW + ii) * RPI + drow;
+      kdma[ii] = (uint32_t)drow * k_row_bytes + (uint32_t)((dp ^ ((r / RPB) % CPR)) * 16);
+    }
+    vdma = (uint32_t)drow * v_row_bytes + (uint32_t)((dp ^ (4 * ((drow / RPB) % (CPR / 4)))) * 16);
+  }
+  // tile `buf` of K (is_v = 0) or V (is_v = 1): instruction ii of this wavefront; the
+  // first 32 rows of the tile come from key rows key_a.., the last 32 from key_b..
+  auto dma = [&](int is_v, int ii, int buf, int key_a, int key_b) __attribute__((always_inline)) {
+    const int half = wave / (NW / 2), wi = wave % (NW / 2);
+    const int krow = (half ? key_b : key_a) + (wi * IPW + ii) * RPI;
+    const uint32_t voffset =
+        is_v ? vdma + (uint32_t)krow * v_row_bytes : kdma[ii] + (uint32_t)krow * k_row_bytes;
+    const uint32_t dst = smem_lds + (uint32_t)((2 * is_v + buf) * TILE_B + (wave * IPW + ii) * 1024);
+    // (the compiler does not see this instruction's LDS write, so it adds no waits of
+    // its own: completion is awaited explicitly before the barrier that publishes the tile)
+    if (is_v)
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                   :: "s"(dst), "v"(voffset), "s"(v_rs) : "memory");
+    else
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                   :: "s"(dst), "v"(voffset), "s"(k_rs) : "memory");
   };
-  auto store_k1 = [&](const Stage<KCH> &st, int it) {
-    *reinterpret_cast<u32x4_t *>(sK + (k_r0 + it * K_R_STEP) * SK + k_c) = st.r[it];
-  };
-  // V: the tile is staged in two halves of BLK/2 keys.  Sub-tile `it` of this thread lies
-  // in half (v_kg0 + it * V_KG_STEP) / KGH: with VIT == 2 that is `it`, with VIT == 1 it is
-  // uniform per wavefront.  Each sub-tile is 4 loads (keys) and 4 transposed word pairs.
-  constexpr int KGH = BLK / 8;  // key groups (of 4 keys) per half
-  static_assert(VIT == 1 || (VIT == 2 && V_KG_STEP == KGH), "V staging layout");
-  auto v_half_of = [&](int it) -> int { return (v_kg0 + it * V_KG_STEP) / KGH; };
-  auto load_v1 = [&](Stage<4> &st, int it, int e, int kv0) {
-    st.r[e] = __builtin_amdgcn_raw_buffer_load_b128(
-        v_rs, v_off0 + (uint32_t)(kv0 + it * V_KG_STEP * 4 + e) * v_row_bytes, 0, 0);
-  };
-  // word pair wd (d = 2wd, 2wd+1) of the 4 keys of sub-tile `it`
-  auto store_vt1 = [&](const Stage<4> &st, int it, int wd) {
-    // 4-key chunk c of a 16-key group is stored at chunk position (0,2,1,3)[c]
-    const int kg = v_kg0 + it * V_KG_STEP;
-    const int pos = (kg & ~3) | ((kg & 1) << 1) | ((kg >> 1) & 1);
-    uint16_t *dst = sVT + (v_dg * 8 + 2 * wd) * SV + pos * 4;
-    u32x2_t even, odd;
-    even.x = __builtin_amdgcn_perm(st.r[1][wd], st.r[0][wd], 0x05040100u);  // lo16(k0) | lo16(k1)<<16
-    even.y = __builtin_amdgcn_perm(st.r[3][wd], st.r[2][wd], 0x05040100u);
-    odd.x = __builtin_amdgcn_perm(st.r[1][wd], st.r[0][wd], 0x07060302u);   // hi16(k0) | hi16(k1)<<16
-    odd.y = __builtin_amdgcn_perm(st.r[3][wd], st.r[2][wd], 0x07060302u);
-    *reinterpret_cast<u32x2_t *>(dst) = even;
-    *reinterpret_cast<u32x2_t *>(dst + SV) = odd;
-  };
-  // Whole-half helpers.  `mine(half)`: does this thread stage anything of that half?
-  // (VIT == 2: always, sub-tile it == half; VIT == 1: only if its sub-tile lies there.)
-  auto v_it_of = [&](int half) -> int { return VIT == 2 ? half : 0; };
-  auto v_mine = [&](int half) -> bool { return VIT == 2 ? true : v_half_of(0) == half; };
 
   // ---- Q fragments (B operand of S^T = K Q^T), kept in registers ----------------
   const int qrow = qb * BLK + wave * 32 + l32;
@@ -276,89 +296,62 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   const size_t row = (size_t)bh * Nb + qb;
   const int cnt = min(kept_count[row], Nb);
   const int *idx = kept_idx + row * Nb;
-  // kept indices are clamped into [0, Nb) so that a bad list cannot leave the tensors
-  auto kept = [&](int c) -> int { return min(max(idx[min(c, cnt - 1)], 0), Nb - 1); };
+  // First key row of 32-key slice sigma of the concatenated kept blocks.  Kept indices are
+  // clamped into [0, Nb) so that a bad list cannot leave the tensors; slices before the
+  // first and after the last repeat the nearest real one (their data is never used).
+  auto slice_key0 = [&](int sigma) -> int {
+    sigma = max(sigma, 0);
+    const int e = min(sigma / NSL, cnt - 1);
+    return min(max(idx[e], 0), Nb - 1) * BLK + (sigma % NSL) * 32;
+  };
 
-  // ---- prologue: first kept block into LDS ---------------------------------------------
-  int j_cur = 0, j_next = 0;
-  if (cnt > 0) {
-    j_cur = kept(0);
-    j_next = kept(1);
-    Stage<KCH> kst;
-#pragma unroll
-    for (int it = 0; it < KCH; ++it) load_k1(kst, it, j_cur * BLK);
-#pragma unroll
-    for (int it = 0; it < KCH; ++it) store_k1(kst, it);
-#pragma unroll
-    for (int it = 0; it < VIT; ++it) {
-      Stage<4> vst;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) load_v1(vst, it, e, j_cur * BLK);
-#pragma unroll
-      for (int wd = 0; wd < 4; ++wd) store_vt1(vst, it, wd);
-    }
-  }
-  __syncthreads();
-
-  // LDS read bases of this lane
-  const uint16_t *sK_rd = sK + l32 * SK + hf * 8;
-  const uint16_t *sV_rd = sVT + l32 * SV + hf * 8;
-
-  // ---- the loop over kept key blocks --------------------------------------------------------
-  // A key block is consumed in NSL slices of 32 keys, software-pipelined.  The MFMAs of one
-  // key block form a fixed stream of SEQ instructions:
-  //   for sl = 0 .. NSL-1:  B(sl): S^T(sl+1), KS MFMAs on K fragments   (not for the last sl)
-  //                         C(sl): O^T += V^T P^T(sl), NPV MFMAs on V^T fragments
-  //   W: S^T(slice 0) of the NEXT key block, KS MFMAs
-  // Every MFMA takes its A operand from a ring of PF registers filled by 16-byte LDS reads
-  // that run PF stream positions ahead, across phase boundaries and across the loop
-  // back-edge; only the two barriers (where the LDS contents change) restart the ring.
-  // The instruction order written here is the intended issue order (sched_barrier fences).
-  // After each MFMA comes a little VALU work that runs in its shadow:
-  //   in B(sl): exponentials / bf16 rounding / row sum of a few elements of slice sl
-  //   in C(sl): part of the maximum of S^T(sl+1); the rare move of the reference exponent
-  //             follows the phase
-  // and at most one staging operation for the next key block:
-  //   K loads and V loads of half 0 in C(0) (in B(0) when NSL == 2); V loads of half 1 in C(NSL-2)
-  //   barrier A before C(NSL-2): every wave has read all of sK and V^T half 0
-  //   K stores and V^T half-0 stores in C(NSL-2)
-  //   barrier B before W: every wave has read V^T half 1; new sK / half 0 visible
-  //   V^T half-1 stores in W; they are first read after the next barrier A
-  constexpr int NSL = BLK / 32;           // slices per key block
+  // ---- the stream of MFMAs -----------------------------------------------------------------
+  // The kept key blocks are one sequence of 32-key slices sigma = 0, 1, ...  Per slice:
+  //   B(sigma): S^T(sigma+1), KS MFMAs on K fragments; in their shadow the exponentials,
+  //             bf16 rounding and row sum of slice sigma
+  //   C(sigma): O^T += V^T P^T(sigma), NPV MFMAs on V^T fragments; in their shadow the
+  //             maximum of S^T(sigma+1); the rare move of the reference exponent follows
+  // K and V arrive in stages of 64 rows (two slices), double-buffered, by LDS-direct
+  // loads that are issued two slices before their first use.  K stage i holds slices
+  // (2i, 2i+1), V stage i holds slices (2i-1, 2i): with this skew the last read of a K
+  // stage (in B(2i)) and of a V stage (in C(2i)) are adjacent, ONE barrier per two slices
+  // retires both, and every B phase has an S^T to overlap its exponentials with.
+  //   ... B(2i) C(2i) | wait for own loads, barrier | B(2i+1) [issue stage i+2] C(2i+1) ...
+  // The loop body covers 4 slices (2 stages) so that buffer indices are constants.  Every
+  // MFMA takes its A operand from a ring of PF registers filled by LDS reads that run PF
+  // stream positions ahead, across phases and the loop back-edge; only the barriers
+  // restart the ring.  The instruction order written here is the intended issue order.
   constexpr int NPV = 2 * DT;             // MFMAs of one slice's O^T update
   constexpr int STEP = KS + NPV;
-  constexpr int G_A = (NSL - 2) * STEP + KS;       // stream position of barrier A: C(NSL-2)
-  constexpr int G_W = (NSL - 1) * STEP + NPV;      // stream position of barrier B: W
-  constexpr int SEQ = G_W + KS;
-  constexpr int PF = HEART_ATTN_PF < KS ? HEART_ATTN_PF : KS;  // LDS reads in flight ahead of the MFMAs
-  static_assert(16 % KS == 0 && (NSL == 2 || NSL == 4) && SEQ % PF == 0 && PF <= KS &&
-                    PF <= NPV, "stream layout");
+  constexpr int SEQ = 4 * STEP;
+  constexpr int G_B0 = STEP, G_B1 = 3 * STEP;  // stream positions right after the barriers
+  constexpr int PF = HEART_ATTN_PF < KS ? HEART_ATTN_PF : KS;
+  static_assert(16 % KS == 0 && SEQ % PF == 0 && PF <= KS && PF <= NPV, "stream layout");
 
-  // A-operand fragment of stream position g (g >= SEQ: the next key block's stream)
-  auto fetch = [&](int g) -> u32x4_t {
+  // A-operand fragment of stream position g.  Slice q (0..3) of the body: its V and the
+  // K of slice q+1 both live in buffer ((q+1)/2)%2, rows ((q+1)%2)*32.
+  auto fetch = [&](int g) __attribute__((always_inline)) -> u32x4_t {
     g %= SEQ;
-    const int sl = g / STEP, r = g % STEP;
-    if (sl < NSL - 1) {
-      if (r < KS)  // B(sl): K fragment of slice sl+1, k-step r
-        return *reinterpret_cast<const u32x4_t *>(sK_rd + (sl + 1) * 32 * SK + r * 16);
-      // C(sl): 8 keys of slice sl for MFMA m (s2 = m / DT, d tile m % DT): key positions
-      // sl*32 + 16*s2 + 8*hf .. +7 (see header)
-      const int m = r - KS;
-      return *reinterpret_cast<const u32x4_t *>(sV_rd + (m % DT) * 32 * SV + sl * 32 + 16 * (m / DT));
-    }
-    if (r < NPV)  // C(NSL-1)
-      return *reinterpret_cast<const u32x4_t *>(sV_rd + (r % DT) * 32 * SV + sl * 32 + 16 * (r / DT));
-    return *reinterpret_cast<const u32x4_t *>(sK_rd + (r - NPV) * 16);  // W: slice 0
+    const int n = g / STEP + 1, r = g % STEP;
+    const int buf = (n >> 1) & 1, row0 = (n & 1) * 32;
+    if (r < KS)
+      return *reinterpret_cast<const u32x4_t *>(smem + buf * TILE_B + row0 * ROWB + koff[r]);
+    const int m = r - KS;
+    const unsigned char *p = smem + (2 + buf) * TILE_B + (row0 + 16 * (m / DT)) * ROWB + voff[m % DT];
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4_t *)(p));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4_t *)(p + 8 * ROWB));
+    const u32x2_t a = __builtin_bit_cast(u32x2_t, lo), c = __builtin_bit_cast(u32x2_t, hi);
+    return u32x4_t{a.x, a.y, c.x, c.y};
   };
   Frag8 ring[PF];
-  // after the MFMA at position g: start the read for position g + PF unless a barrier
-  // lies in between (then the ring is refilled after that barrier)
-  auto prefetch_after = [&](int g) {
-    const int t = g + PF;
-    const bool crosses = (g < G_A && t >= G_A) || (g < G_W && t >= G_W);
-    if (!crosses) ring[t % PF].u = fetch(t);
+  auto prefetch_after = [&](int g) __attribute__((always_inline)) {
+    const int t2 = g + PF;
+    const bool crosses = (g < G_B0 && t2 >= G_B0) || (g < G_B1 && t2 >= G_B1);
+    if (!crosses) ring[t2 % PF].u = fetch(t2);
   };
-  auto refill = [&](int g0) {
+  auto refill = [&](int g0) __attribute__((always_inline)) {
 #pragma unroll
     for (int j = 0; j < PF; ++j) ring[(g0 + j) % PF].u = fetch(g0 + j);
   };
@@ -373,7 +366,7 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   // 24 cycles of a wave's own VALU work hide behind one of its MFMAs and a slot that
   // exceeds that stalls the matrix pipeline: B slots take 3 micro-ops, C slots 2.
   float xt0 = 0.f, xt1 = 0.f;  // the pair in flight
-  auto exp_uop = [&](const f32x16_t &x, int u, float m_sub) {
+  auto exp_uop = [&](const f32x16_t &x, int u, float m_sub) __attribute__((always_inline)) {
     const int r = 2 * (u >> 2), st = u & 3;
     // (the empty asm statements pin each result to its slot: without them the compiler
     // sinks the whole computation to its first use, out of the MFMA shadow)
@@ -397,37 +390,35 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   };
   constexpr int UB = 24 / KS;        // micro-ops per B slot: pairs 0..5 of the slice
   constexpr int UC = 8 / DT;         // micro-ops per C slot m < DT: pairs 6..7
-  // B / W: S^T(slice sl) into sacc[sl & 1], stream positions g0 .. g0+KS-1; with_exp:
-  // interleave the weights of slice sl-1.  extra(slot) injects staging work.
-  auto qk_step = [&](int sl, int g0, bool with_exp, float m_sub, auto &&extra) {
+  // B: S^T into sacc[dst], stream positions g0 .. g0+KS-1, with the weights of the slice in
+  // sacc[dst ^ 1] interleaved.  extra(slot) injects the loads of a later stage.
+  auto qk_step = [&](int dst, int g0, float m_sub, auto &&extra) __attribute__((always_inline)) {
     f32x16_t acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    const f32x16_t &prev = sacc[(sl + 1) & 1];
+    const f32x16_t &prev = sacc[dst ^ 1];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[(g0 + ks) % PF].v, qf[ks].v, acc, 0, 0, 0);
       prefetch_after(g0 + ks);
-      if (with_exp) {
 #pragma unroll
-        for (int u = 0; u < UB; ++u) exp_uop(prev, ks * UB + u, m_sub);
-      }
+      for (int u = 0; u < UB; ++u) exp_uop(prev, ks * UB + u, m_sub);
       extra(ks);
       __builtin_amdgcn_sched_barrier(0);
     }
-    sacc[sl & 1] = acc;
+    sacc[dst] = acc;
   };
-  // keys past the end of a ragged last key block get no weight
-  auto mask_slice = [&](f32x16_t &x, int sl, int nvalid) {
+  // keys at or past row `nvalid` of the slice (end of a ragged last key block) get no weight
+  auto mask_slice = [&](f32x16_t &x, int nvalid) __attribute__((always_inline)) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int key = sl * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+      const int key = 8 * (r >> 2) + 4 * hf + (r & 3);
       if (key >= nvalid) x[r] = -__builtin_inff();
     }
   };
   // maximum of one accumulator over this lane's 16 keys, in 4 partial steps so that it
   // can be spread over MFMA slots; step i folds elements 4i .. 4i+3
-  auto max_part = [&](const f32x16_t &x, int i, float m) -> float {
+  auto max_part = [&](const f32x16_t &x, int i, float m) __attribute__((always_inline)) -> float {
     m = fmaxf(fmaxf(m, x[4 * i]), x[4 * i + 1]);       // v_max3_f32
     return fmaxf(fmaxf(m, x[4 * i + 2]), x[4 * i + 3]);  // v_max3_f32
   };
@@ -437,7 +428,7 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   // exponentials then stay below 2^slack and the accumulator rescale is skipped for
   // most slices.  A slice whose keys are all past the end has maximum -inf and never
   // moves it.  Returns the exponent to subtract (0 while every logit so far was masked).
-  auto finish_max = [&](float m_loc) -> float {
+  auto finish_max = [&](float m_loc) __attribute__((always_inline)) -> float {
     uint32_t sw0, sw1;
     swap_halves32(__float_as_uint(m_loc), sw0, sw1);
     m_loc = fmaxf(__uint_as_float(sw0), __uint_as_float(sw1));
@@ -456,114 +447,132 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
     }
     return m_ref == -__builtin_inff() ? 0.f : m_ref;
   };
-  // C: O^T += V^T P^T(slice sl), stream positions g0 .. g0+NPV-1.  The first DT slots
-  // finish the weights of the slice (pairs 6..7, consumed by the second half of the
-  // MFMAs); with_max: the second half of the slots folds the maximum of S^T(sl+1), whose
+  // C: O^T += V^T P^T of the slice in sacc[cur], stream positions g0 .. g0+NPV-1.  The first
+  // DT slots finish the weights of the slice (pairs 6..7, consumed by the second half of
+  // the MFMAs); the second half of the slots folds the maximum of sacc[cur ^ 1], whose
   // MFMAs were issued before this phase and have drained by then.
-  auto pv_step = [&](int sl, int g0, bool with_max, float m_sub, auto &&extra) -> float {
+  auto pv_step = [&](int cur, int g0, float m_sub) __attribute__((always_inline)) -> float {
     float m_loc = -__builtin_inff();
-    const f32x16_t &nx = sacc[(sl + 1) & 1];
-    const f32x16_t &cur = sacc[sl & 1];
+    const f32x16_t &nx = sacc[cur ^ 1];
+    const f32x16_t &cx = sacc[cur];
 #pragma unroll
     for (int m = 0; m < NPV; ++m) {
       o[m % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[(g0 + m) % PF].v, pf[m / DT].v, o[m % DT], 0, 0, 0);
       prefetch_after(g0 + m);
       if (m < DT) {
 #pragma unroll
-        for (int u = 0; u < UC; ++u) exp_uop(cur, 24 + m * UC + u, m_sub);
+        for (int u = 0; u < UC; ++u) exp_uop(cx, 24 + m * UC + u, m_sub);
       }
-      if (with_max && m >= DT) {
+      if (m >= DT) {
 #pragma unroll
         for (int i = 0; i < 4 / DT; ++i) m_loc = max_part(nx, (m - DT) * (4 / DT) + i, m_loc);
       }
-      extra(m);
       __builtin_amdgcn_sched_barrier(0);
     }
     return m_loc;
   };
   auto no_extra = [](int) {};
-  // maximum of slice 0 of a key block right after its S^T (prologue and W)
-  auto slice0_max = [&](int nvalid) -> float {
-    if (nvalid < BLK) mask_slice(sacc[0], 0, nvalid);
+  auto wait_loads_and_barrier = [&]() __attribute__((always_inline)) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+  };
+
+  if (cnt > 0) {
+    // ---- prologue: stages 0 and 1 in flight, S^T and maximum of slice 0 --------------------
+    {
+      const int k0 = slice_key0(0), k1 = slice_key0(1), k2 = slice_key0(2), k3 = slice_key0(3);
+#pragma unroll
+      for (int ii = 0; ii < IPW; ++ii) dma(0, ii, 0, k0, k1);
+#pragma unroll
+      for (int ii = 0; ii < IPW; ++ii) dma(1, ii, 0, k0, k0);
+#pragma unroll
+      for (int ii = 0; ii < IPW; ++ii) dma(0, ii, 1, k2, k3);
+#pragma unroll
+      for (int ii = 0; ii < IPW; ++ii) dma(1, ii, 1, k1, k2);
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * IPW) : "memory");  // stage 0 has landed
+      __syncthreads();
+      f32x16_t acc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        Frag8 a;
+        a.u = fetch(3 * STEP + ks);  // K of slice 0: buffer 0, rows 0
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, qf[ks].v, acc, 0, 0, 0);
+      }
+      sacc[0] = acc;
+      const int nv = N - k0;
+      if (nv < 32) mask_slice(sacc[0], nv);
+    }
     float m_loc = -__builtin_inff();
 #pragma unroll
     for (int i = 0; i < 4; ++i) m_loc = max_part(sacc[0], i, m_loc);
-    return finish_max(m_loc);
-  };
+    float m_sub = finish_max(m_loc);
+    refill(0);
 
-  float m_sub = 0.f;
-  if (cnt > 0) {
-    refill(G_W);
-    qk_step(0, G_W, false, 0.f, no_extra);
-    m_sub = slice0_max(min(BLK, N - j_cur * BLK));
-  }
-  for (int c = 0; c < cnt; ++c) {
-    // After the last kept block the "next" block is the current one again: the staging
-    // then re-stages data nobody reads, which keeps the loop branch-free.
-    const int j_next2 = kept(c + 2);
-    const int nvalid_cur = min(BLK, N - j_cur * BLK);
-    const int nvalid_next = min(BLK, N - j_next * BLK);
-    const int kv_next = j_next * BLK;
-    Stage<KCH> kreg;
-    Stage<4> v0, v1;  // V sub-tiles of half 0 and half 1 of the next key block
+    const int T = cnt * NSL / 2;  // stages
+    for (int st = 0; st < T; st += 2) {
+      const int s0 = 2 * st;  // first slice of the body
+      // ---- slice s0: B, C, then the barrier that retires K stage st and V stage st ----
+      qk_step(1, 0, m_sub, no_extra);
+      {
+        const int nv = N - slice_key0(s0 + 1);
+        if (nv < 32) mask_slice(sacc[1], nv);
+      }
+      m_loc = pv_step(0, KS, m_sub);
+      m_sub = finish_max(m_loc);
+      wait_loads_and_barrier();
+      refill(G_B0);
+      // ---- slice s0+1; stage st+2 -> buffers 0 ----
+      {
+        const int ka = slice_key0(s0 + 4), kb = slice_key0(s0 + 5), va = slice_key0(s0 + 3);
+        qk_step(0, STEP, m_sub, [&](int ks) {
 #pragma unroll
-    for (int sl = 0; sl < NSL; ++sl) {
-      // ---- B(sl) ----
-      if (sl + 1 < NSL) {
-        qk_step(sl + 1, sl * STEP, true, m_sub, [&](int ks) {
-          if (NSL == 2 && sl == 0) {  // short key blocks: C(0) already stores, so load here
-#pragma unroll
-            for (int it = 0; it < KCH; ++it)
-              if (it * KS / KCH == ks) load_k1(kreg, it, kv_next);
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (e * KS / 4 == ks && v_mine(0)) load_v1(v0, v_it_of(0), e, kv_next);
-          }
+          for (int ii = 0; ii < 2 * IPW; ++ii)
+            if (ii * KS / (2 * IPW) == ks) {
+              if (ii < IPW) dma(0, ii, 0, ka, kb);
+              else dma(1, ii - IPW, 0, va, ka);
+            }
         });
-        if (nvalid_cur < BLK) mask_slice(sacc[(sl + 1) & 1], sl + 1, nvalid_cur);
-      } else {
-        // last slice: no S^T left to overlap the first 6 pairs of its weights with
-#pragma unroll
-        for (int u = 0; u < 24; ++u) exp_uop(sacc[sl & 1], u, m_sub);
       }
-      if (sl == NSL - 2) {
-        __syncthreads();  // barrier A
-        refill(G_A);
+      {
+        const int nv = N - slice_key0(s0 + 2);
+        if (nv < 32) mask_slice(sacc[0], nv);
       }
-      // ---- C(sl) ----
-      const int g_c = sl * STEP + (sl + 1 < NSL ? KS : 0);
-      const float m_loc = pv_step(sl, g_c, sl + 1 < NSL, m_sub, [&](int m) {
-        if (NSL > 2 && sl == 0) {  // K loads and V half-0 loads of the next key block, spread over the slots
+      m_loc = pv_step(1, STEP + KS, m_sub);
+      m_sub = finish_max(m_loc);
+      if (NSL == 2 && st + 1 >= T) break;
+      // ---- slice s0+2: B, C, barrier retiring K stage st+1 and V stage st+1 ----
+      qk_step(1, 2 * STEP, m_sub, no_extra);
+      {
+        const int nv = N - slice_key0(s0 + 3);
+        if (nv < 32) mask_slice(sacc[1], nv);
+      }
+      m_loc = pv_step(0, 2 * STEP + KS, m_sub);
+      m_sub = finish_max(m_loc);
+      wait_loads_and_barrier();
+      refill(G_B1);
+      // ---- slice s0+3; stage st+3 -> buffers 1 ----
+      {
+        const int ka = slice_key0(s0 + 6), kb = slice_key0(s0 + 7), va = slice_key0(s0 + 5);
+        qk_step(0, 3 * STEP, m_sub, [&](int ks) {
 #pragma unroll
-          for (int it = 0; it < KCH; ++it)
-            if (it * NPV / KCH == m) load_k1(kreg, it, kv_next);
-          if (m >= NPV - 4 && v_mine(0)) load_v1(v0, v_it_of(0), m - (NPV - 4), kv_next);
-        }
-        if (sl == NSL - 2) {
-          // K stores, spread; V^T half-0 stores (one word pair per slot); V loads, half 1
-#pragma unroll
-          for (int it = 0; it < KCH; ++it)
-            if (it * NPV / KCH == m) store_k1(kreg, it);
-          if (m >= NPV - 4 && v_mine(0)) store_vt1(v0, v_it_of(0), m - (NPV - 4));
-          if (m >= NPV - 4 && v_mine(1)) load_v1(v1, v_it_of(1), m - (NPV - 4), kv_next);
-        }
-      });
-      if (sl + 1 < NSL) m_sub = finish_max(m_loc);
+          for (int ii = 0; ii < 2 * IPW; ++ii)
+            if (ii * KS / (2 * IPW) == ks) {
+              if (ii < IPW) dma(0, ii, 1, ka, kb);
+              else dma(1, ii - IPW, 1, va, ka);
+            }
+        });
+      }
+      {
+        const int nv = N - slice_key0(s0 + 4);
+        if (nv < 32) mask_slice(sacc[0], nv);
+      }
+      m_loc = pv_step(1, 3 * STEP + KS, m_sub);
+      m_sub = finish_max(m_loc);
     }
-    // barrier B
-    __syncthreads();
-    refill(G_W);
-    // ---- W: S^T(slice 0) of the next key block, with the V^T half-1 stores ----
-    qk_step(0, G_W, false, 0.f, [&](int ks) {
-      if (ks < 4 && v_mine(1)) store_vt1(v1, v_it_of(1), ks);
-    });
-    if (KS < 4 && v_mine(1)) {
-#pragma unroll
-      for (int wd = KS; wd < 4; ++wd) store_vt1(v1, v_it_of(1), wd);
-    }
-    m_sub = slice0_max(nvalid_next);
-    j_cur = j_next;
-    j_next = j_next2;
+    // loads of stages past the end may still be in flight towards LDS
+    wait_loads_and_barrier();
   }
 
   // ---- epilogue: normalise, stage through LDS, coalesced bf16 store -----------------------
@@ -572,7 +581,7 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   if (lse && hf == 0 && qrow < N)
     lse[(size_t)bh * N + qrow] =
         l_tot > 0.f ? (m_ref + log2f(l_tot)) * 0.6931471805599453f : -__builtin_inff();
-  uint16_t *sO = sK;  // [BLK][SK]; sK is idle after the last barrier
+  uint16_t *sO = reinterpret_cast<uint16_t *>(smem);  // [BLK][SO]
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -580,17 +589,20 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
       u32x2_t pk;
       pk.x = cvt_pk_bf16(o[dt][4 * g + 0] * inv, o[dt][4 * g + 1] * inv);
       pk.y = cvt_pk_bf16(o[dt][4 * g + 2] * inv, o[dt][4 * g + 3] * inv);
-      *reinterpret_cast<u32x2_t *>(sO + (wave * 32 + l32) * SK + dt * 32 + 8 * g + 4 * hf) = pk;
+      *reinterpret_cast<u32x2_t *>(sO + (wave * 32 + l32) * SO + dt * 32 + 8 * g + 4 * hf) = pk;
     }
   __syncthreads();
   uint16_t *obase = out + b * osb + h * osh;
+  constexpr int OCH = (BLK * CPR) / NT;  // 16-byte chunks of the output per thread
+  constexpr int O_R_STEP = NT / CPR;
+  const int o_r0 = t / CPR, o_c = (t % CPR) * 8;
 #pragma unroll
-  for (int it = 0; it < KCH; ++it) {
-    const int r = k_r0 + it * K_R_STEP;
+  for (int it = 0; it < OCH; ++it) {
+    const int r = o_r0 + it * O_R_STEP;
     const int n = qb * BLK + r;
     if (n < N)
-      *reinterpret_cast<u32x4_t *>(obase + (long long)n * osn + k_c) =
-          *reinterpret_cast<const u32x4_t *>(sO + r * SK + k_c);
+      *reinterpret_cast<u32x4_t *>(obase + (long long)n * osn + o_c) =
+          *reinterpret_cast<const u32x4_t *>(sO + r * SO + o_c);
   }
 }
 
@@ -600,7 +612,7 @@ static int launch_attn_t(const heart_shape &s, const void *q, const void *k, con
                          float *lse, int *order, hipStream_t st) {
   const int Nb = (s.N + BLK - 1) / BLK;
   const int BH = s.B * s.H;
-  const size_t lds = ((size_t)BLK * (D + 8) + (size_t)D * (BLK + 8)) * 2;
+  const size_t lds = 4 * (size_t)kStageRows * D * 2;  // >= BLK * (D + 8) * 2 of the output staging
   auto kern = attn_kernel<D, BLK>;
   static bool attr_set = false;  // the attribute is per function, set once per process
   if (!attr_set) {
