@@ -283,6 +283,13 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
       qf[ks].u = __builtin_amdgcn_raw_buffer_load_b128(q_rs, q_off + ks * 32, 0, 0);
+    // fold the softmax scale and log2(e) into Q once: S^T then comes out of the matrix
+    // cores in log2 units and no per-logit multiply is left on the VALU
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+        qf[ks].u[w] = cvt_pk_bf16(bf16lo(qf[ks].u[w]) * scale_log2e, bf16hi(qf[ks].u[w]) * scale_log2e);
   }
 
   f32x16_t o[DT];
@@ -291,19 +298,30 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
   float m_ref = -__builtin_inff();  // reference exponent (log2 domain) of the running sums
-  float l_run = 0.f;                // running sum over this lane's keys, relative to m_ref
+  // S^T accumulators start from -m_ref instead of zero, so they hold logits relative to
+  // the reference exponent and go into the exponential as they are
+  f32x16_t cinit;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) cinit[r] = 0.f;
+  float l_run = 0.f;  // running sum over this lane's keys, relative to m_ref
 
   const size_t row = (size_t)bh * Nb + qb;
   const int cnt = min(kept_count[row], Nb);
   const int *idx = kept_idx + row * Nb;
-  // First key row of 32-key slice sigma of the concatenated kept blocks.  Kept indices are
-  // clamped into [0, Nb) so that a bad list cannot leave the tensors; slices before the
-  // first and after the last repeat the nearest real one (their data is never used).
-  auto slice_key0 = [&](int sigma) -> int {
-    sigma = max(sigma, 0);
-    const int e = min(sigma / NSL, cnt - 1);
-    return min(max(idx[e], 0), Nb - 1) * BLK + (sigma % NSL) * 32;
-  };
+  // The kept blocks are consumed as one sequence of 32-key slices.  Kept indices are
+  // clamped into [0, Nb) so that a bad list cannot leave the tensors; entries past the
+  // end of the list repeat the last one (their data is never used).
+  auto kept = [&](int e) -> int { return min(max(idx[min(max(e, 0), cnt - 1)], 0), Nb - 1); };
+  // The loop body covers 4 slices starting at slice s0 (list entry eb) and looks ahead up
+  // to slice s0+7: the block indices of entries eb .. eb+NE-1 are held in scalar registers
+  // and advance by EPB entries per body.  New entries are loaded right before a barrier:
+  // a scalar load can only be awaited together with all outstanding LDS reads, and there
+  // the pipeline of LDS reads is drained anyway.
+  constexpr int EPB = 4 / NSL;      // list entries per loop body
+  constexpr int NE = 7 / NSL + 1;   // entries a body can refer to
+  int jb[NE];
+  // first key row of slice s0 + rel (rel = 0 .. 7) of the current body
+  auto key_of = [&](int rel) -> int { return jb[rel / NSL] * BLK + (rel % NSL) * 32; };
 
   // ---- the stream of MFMAs -----------------------------------------------------------------
   // The kept key blocks are one sequence of 32-key slices sigma = 0, 1, ...  Per slice:
@@ -359,26 +377,22 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   f32x16_t sacc[2];  // S^T of the slice being exponentiated and of the next one
   Frag8 pf[2];       // P^T of the current slice: [s2] = rows 8*s2 .. 8*s2+7 of the accumulator
 
-  // Weights of one slice relative to the reference exponent, rounded to bf16 for the second
-  // contraction (the row sum adds the unrounded fp32 weights).  The work on the 8
-  // element pairs of a lane is cut into 32 micro-ops of about 8 VALU cycles each (pair
-  // p = u / 4: two FMAs, exponential, exponential, convert + row sum), because only about
-  // 24 cycles of a wave's own VALU work hide behind one of its MFMAs and a slot that
-  // exceeds that stalls the matrix pipeline: B slots take 3 micro-ops, C slots 2.
+  // Weights of one slice: exp2 of the accumulator (already relative to the reference
+  // exponent), rounded to bf16 for the second contraction; the row sum adds the unrounded
+  // fp32 weights.  The 8 element pairs of a lane are 24 micro-ops (exponential,
+  // exponential, convert + row sum) that are pinned, a few at a time, behind MFMAs: only
+  // about 24 cycles of a wave's own VALU work hide behind one of its MFMAs, and a slot
+  // that exceeds that stalls the matrix pipeline.
   float xt0 = 0.f, xt1 = 0.f;  // the pair in flight
-  auto exp_uop = [&](const f32x16_t &x, int u, float m_sub) __attribute__((always_inline)) {
-    const int r = 2 * (u >> 2), st = u & 3;
+  auto exp_uop = [&](const f32x16_t &x, int u) __attribute__((always_inline)) {
+    const int r = 2 * (u / 3), st = u % 3;
     // (the empty asm statements pin each result to its slot: without them the compiler
     // sinks the whole computation to its first use, out of the MFMA shadow)
     if (st == 0) {
-      xt0 = __builtin_fmaf(x[r], scale_log2e, -m_sub);
-      xt1 = __builtin_fmaf(x[r + 1], scale_log2e, -m_sub);
-      asm volatile("" : "+v"(xt0), "+v"(xt1));
-    } else if (st == 1) {
-      xt0 = __builtin_amdgcn_exp2f(xt0);
+      xt0 = __builtin_amdgcn_exp2f(x[r]);
       asm volatile("" : "+v"(xt0));
-    } else if (st == 2) {
-      xt1 = __builtin_amdgcn_exp2f(xt1);
+    } else if (st == 1) {
+      xt1 = __builtin_amdgcn_exp2f(x[r + 1]);
       asm volatile("" : "+v"(xt1));
     } else {
       // (plain adds for the row sum: they co-issue with MFMAs, dot instructions do not)
@@ -388,21 +402,20 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
       pf[r / 8].u[(r % 8) / 2] = pk;
     }
   };
-  constexpr int UB = 24 / KS;        // micro-ops per B slot: pairs 0..5 of the slice
-  constexpr int UC = 8 / DT;         // micro-ops per C slot m < DT: pairs 6..7
+  constexpr int UB = 16 / KS;        // micro-ops per B slot (16 of the 24 in B)
+  constexpr int UC = 8 / DT;         // micro-ops per C slot m < DT (the other 8)
   // B: S^T into sacc[dst], stream positions g0 .. g0+KS-1, with the weights of the slice in
   // sacc[dst ^ 1] interleaved.  extra(slot) injects the loads of a later stage.
-  auto qk_step = [&](int dst, int g0, float m_sub, auto &&extra) __attribute__((always_inline)) {
+  auto qk_step = [&](int dst, int g0, auto &&extra) __attribute__((always_inline)) {
     f32x16_t acc;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     const f32x16_t &prev = sacc[dst ^ 1];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[(g0 + ks) % PF].v, qf[ks].v, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[(g0 + ks) % PF].v, qf[ks].v,
+                                                    ks == 0 ? cinit : acc, 0, 0, 0);
       prefetch_after(g0 + ks);
 #pragma unroll
-      for (int u = 0; u < UB; ++u) exp_uop(prev, ks * UB + u, m_sub);
+      for (int u = 0; u < UB; ++u) exp_uop(prev, ks * UB + u);
       extra(ks);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -422,36 +435,42 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
     m = fmaxf(fmaxf(m, x[4 * i]), x[4 * i + 1]);       // v_max3_f32
     return fmaxf(fmaxf(m, x[4 * i + 2]), x[4 * i + 3]);  // v_max3_f32
   };
-  // Finish the maximum of a slice (combine the two lanes of a query: lane l and l^32 are
-  // exchanged with one v_permlane32_swap) and, rarely, move the reference exponent.
-  // The reference only moves when the slice maximum exceeds it by more than the slack:
-  // exponentials then stay below 2^slack and the accumulator rescale is skipped for
-  // most slices.  A slice whose keys are all past the end has maximum -inf and never
-  // moves it.  Returns the exponent to subtract (0 while every logit so far was masked).
-  auto finish_max = [&](float m_loc) __attribute__((always_inline)) -> float {
-    uint32_t sw0, sw1;
-    swap_halves32(__float_as_uint(m_loc), sw0, sw1);
-    m_loc = fmaxf(__uint_as_float(sw0), __uint_as_float(sw1));
-    const float m_tile = m_loc * scale_log2e;  // scale > 0, so max commutes with scaling
-    const bool bump = m_tile > m_ref + kRescaleSlack ||
-                      (m_ref == -__builtin_inff() && m_tile > -__builtin_inff());
-    if (__any(bump)) {
-      const float m_new = bump ? m_tile : m_ref;
-      const float alpha = bump ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.f;
+  // After the maximum m_rel of a slice (over this lane's keys, relative to the reference
+  // exponent): the reference only moves when some logit exceeds it by more than the slack,
+  // so exponentials stay below 2^slack and almost every slice takes the short path (one
+  // compare per lane and a wave-wide vote).  The long path combines the two lanes of each
+  // query (lane l and l^32, one v_permlane32_swap), moves the reference of the queries
+  // that need it, rescales their sums, makes the not yet exponentiated slice x relative to
+  // the new reference, and rewrites the accumulator start values.  A slice whose keys are
+  // all past the end has maximum -inf and never moves the reference.
+  auto finish_max = [&](float m_rel, f32x16_t &x) __attribute__((always_inline)) {
+    const bool first = m_ref == -__builtin_inff();
+    if (__any(m_rel > kRescaleSlack || (first && m_rel > -__builtin_inff()))) {
+      uint32_t sw0, sw1;
+      swap_halves32(__float_as_uint(m_rel), sw0, sw1);
+      m_rel = fmaxf(__uint_as_float(sw0), __uint_as_float(sw1));
+      const bool bump = m_rel > kRescaleSlack || (first && m_rel > -__builtin_inff());
+      const float base = first ? 0.f : m_ref;       // what the accumulators are relative to
+      const float delta = bump ? m_rel : 0.f;
+      const float m_new = bump ? base + m_rel : m_ref;
+      const float alpha = bump ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.f;  // 0 the first time
       l_run *= alpha;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) x[r] -= delta;
       m_ref = m_new;
+      const float c0 = m_ref == -__builtin_inff() ? 0.f : -m_ref;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) cinit[r] = c0;
     }
-    return m_ref == -__builtin_inff() ? 0.f : m_ref;
   };
-  // C: O^T += V^T P^T of the slice in sacc[cur], stream positions g0 .. g0+NPV-1.  The first
-  // DT slots finish the weights of the slice (pairs 6..7, consumed by the second half of
-  // the MFMAs); the second half of the slots folds the maximum of sacc[cur ^ 1], whose
-  // MFMAs were issued before this phase and have drained by then.
-  auto pv_step = [&](int cur, int g0, float m_sub) __attribute__((always_inline)) -> float {
+  // C: O^T += V^T P^T of the slice in sacc[cur], stream positions g0 .. g0+NPV-1.  The first DT slots finish the weights of the slice (consumed by the
+  // second half of the MFMAs); the second half of the slots folds the maximum of
+  // sacc[cur ^ 1], whose MFMAs were issued before this phase and have drained by then.
+  auto pv_step = [&](int cur, int g0) __attribute__((always_inline)) -> float {
     float m_loc = -__builtin_inff();
     const f32x16_t &nx = sacc[cur ^ 1];
     const f32x16_t &cx = sacc[cur];
@@ -461,7 +480,7 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
       prefetch_after(g0 + m);
       if (m < DT) {
 #pragma unroll
-        for (int u = 0; u < UC; ++u) exp_uop(cx, 24 + m * UC + u, m_sub);
+        for (int u = 0; u < UC; ++u) exp_uop(cx, 16 + m * UC + u);
       }
       if (m >= DT) {
 #pragma unroll
@@ -480,7 +499,9 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   if (cnt > 0) {
     // ---- prologue: stages 0 and 1 in flight, S^T and maximum of slice 0 --------------------
     {
-      const int k0 = slice_key0(0), k1 = slice_key0(1), k2 = slice_key0(2), k3 = slice_key0(3);
+#pragma unroll
+      for (int e = 0; e < NE; ++e) jb[e] = kept(e);
+      const int k0 = key_of(0), k1 = key_of(1), k2 = key_of(2), k3 = key_of(3);
 #pragma unroll
       for (int ii = 0; ii < IPW; ++ii) dma(0, ii, 0, k0, k1);
 #pragma unroll
@@ -491,9 +512,7 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
       for (int ii = 0; ii < IPW; ++ii) dma(1, ii, 1, k1, k2);
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * IPW) : "memory");  // stage 0 has landed
       __syncthreads();
-      f32x16_t acc;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+      f32x16_t acc = cinit;  // zeros: no reference exponent yet
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         Frag8 a;
@@ -507,26 +526,31 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
     float m_loc = -__builtin_inff();
 #pragma unroll
     for (int i = 0; i < 4; ++i) m_loc = max_part(sacc[0], i, m_loc);
-    float m_sub = finish_max(m_loc);
+    finish_max(m_loc, sacc[0]);
     refill(0);
 
     const int T = cnt * NSL / 2;  // stages
     for (int st = 0; st < T; st += 2) {
-      const int s0 = 2 * st;  // first slice of the body
+      // (body: slices s0 = 2 st .. s0+3, list entry eb = s0 / NSL)
+      int jn[EPB];
       // ---- slice s0: B, C, then the barrier that retires K stage st and V stage st ----
-      qk_step(1, 0, m_sub, no_extra);
+      qk_step(1, 0, no_extra);
       {
-        const int nv = N - slice_key0(s0 + 1);
+        const int nv = N - key_of(1);
         if (nv < 32) mask_slice(sacc[1], nv);
       }
-      m_loc = pv_step(0, KS, m_sub);
-      m_sub = finish_max(m_loc);
+      m_loc = pv_step(0, KS);
+      finish_max(m_loc, sacc[1]);
+#pragma unroll
+      for (int i = 0; i < EPB; ++i) jn[i] = kept(2 * st / NSL + NE + i);
       wait_loads_and_barrier();
+#pragma unroll
+      for (int i = 0; i < EPB; ++i) asm volatile("" : "+s"(jn[i]));  // loaded before the barrier
       refill(G_B0);
       // ---- slice s0+1; stage st+2 -> buffers 0 ----
       {
-        const int ka = slice_key0(s0 + 4), kb = slice_key0(s0 + 5), va = slice_key0(s0 + 3);
-        qk_step(0, STEP, m_sub, [&](int ks) {
+        const int ka = key_of(4), kb = key_of(5), va = key_of(3);
+        qk_step(0, STEP, [&](int ks) {
 #pragma unroll
           for (int ii = 0; ii < 2 * IPW; ++ii)
             if (ii * KS / (2 * IPW) == ks) {
@@ -536,26 +560,26 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
         });
       }
       {
-        const int nv = N - slice_key0(s0 + 2);
+        const int nv = N - key_of(2);
         if (nv < 32) mask_slice(sacc[0], nv);
       }
-      m_loc = pv_step(1, STEP + KS, m_sub);
-      m_sub = finish_max(m_loc);
+      m_loc = pv_step(1, STEP + KS);
+      finish_max(m_loc, sacc[0]);
       if (NSL == 2 && st + 1 >= T) break;
       // ---- slice s0+2: B, C, barrier retiring K stage st+1 and V stage st+1 ----
-      qk_step(1, 2 * STEP, m_sub, no_extra);
+      qk_step(1, 2 * STEP, no_extra);
       {
-        const int nv = N - slice_key0(s0 + 3);
+        const int nv = N - key_of(3);
         if (nv < 32) mask_slice(sacc[1], nv);
       }
-      m_loc = pv_step(0, 2 * STEP + KS, m_sub);
-      m_sub = finish_max(m_loc);
+      m_loc = pv_step(0, 2 * STEP + KS);
+      finish_max(m_loc, sacc[1]);
       wait_loads_and_barrier();
       refill(G_B1);
       // ---- slice s0+3; stage st+3 -> buffers 1 ----
       {
-        const int ka = slice_key0(s0 + 6), kb = slice_key0(s0 + 7), va = slice_key0(s0 + 5);
-        qk_step(0, 3 * STEP, m_sub, [&](int ks) {
+        const int ka = key_of(6), kb = key_of(7), va = key_of(5);
+        qk_step(0, 3 * STEP, [&](int ks) {
 #pragma unroll
           for (int ii = 0; ii < 2 * IPW; ++ii)
             if (ii * KS / (2 * IPW) == ks) {
@@ -565,11 +589,16 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
         });
       }
       {
-        const int nv = N - slice_key0(s0 + 4);
+        const int nv = N - key_of(4);
         if (nv < 32) mask_slice(sacc[0], nv);
       }
-      m_loc = pv_step(1, 3 * STEP + KS, m_sub);
-      m_sub = finish_max(m_loc);
+      m_loc = pv_step(1, 3 * STEP + KS);
+      finish_max(m_loc, sacc[0]);
+      // advance the entry window
+#pragma unroll
+      for (int e = 0; e + EPB < NE; ++e) jb[e] = jb[e + EPB];
+#pragma unroll
+      for (int i = 0; i < EPB; ++i) jb[NE - EPB + i] = jn[i];
     }
     // loads of stages past the end may still be in flight towards LDS
     wait_loads_and_barrier();
