@@ -151,6 +151,22 @@ int heart_block_sparse_attn(const heart_shape *shape, const void *q_bf16, const 
 /* Bytes of workspace heart_block_sparse_attn can use for `shape` (0 if shape is invalid). */
 size_t heart_attn_workspace_bytes(const heart_shape *shape);
 
+/*
+ * Diagnostics for roofline accounting (not part of the method).
+ * heart_ubench_mfma_bf16: n_workgroups workgroups of 4 wavefronts each issue 16 * iters
+ *   v_mfma_f32_32x32x16_bf16 on register operands taken from a_bf16 / b_bf16 (device,
+ *   8192 bf16 each, 16-byte aligned); FLOPs = n_workgroups * 4 * iters * 16 * 32768.
+ *   The sustained clock of the chip depends on the operand bits, so timing this call
+ *   with zeros and with data like a kernel's own gives the nominal and the attainable
+ *   matrix-core rate.  sink: one float (device), practically never written.
+ * heart_ubench_copy: plain device-to-device copy of `bytes` (multiple of 16); moves
+ *   2 * bytes through HBM.  Reference for HBM bandwidth and for scaling hardware
+ *   traffic counters.
+ */
+int heart_ubench_mfma_bf16(const void *a_bf16, const void *b_bf16, int n_workgroups, int iters,
+                           float *sink, void *stream);
+int heart_ubench_copy(const void *src, void *dst, size_t bytes, void *stream);
+
 /* Thread-local message of the last error returned on this thread ("" if none). */
 const char *heart_last_error(void);
 

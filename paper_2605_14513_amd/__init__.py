@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     heart_last_error,
     heart_mask_topp,
     heart_pool_qk,
+    heart_ubench_copy,
+    heart_ubench_mfma_bf16,
     heart_version,
     lib_path,
     load_library,

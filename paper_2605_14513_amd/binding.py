@@ -64,6 +64,10 @@ def load_library() -> ctypes.CDLL:
     for f in (lib.heart_pool_qk, lib.heart_drift, lib.heart_mask_topp,
               lib.heart_block_sparse_attn, lib.heart_version):
         f.restype = ci
+    lib.heart_ubench_mfma_bf16.argtypes = [vp, vp, ci, ci, vp, vp]
+    lib.heart_ubench_mfma_bf16.restype = ci
+    lib.heart_ubench_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    lib.heart_ubench_copy.restype = ci
     lib.heart_last_error.restype = ctypes.c_char_p
     _lib = lib
     return lib
@@ -248,3 +252,28 @@ def heart_block_sparse_attn(q, k, v, block: int, kept_idx, kept_count, scale: fl
                                      _dev(lse, torch.float32, "lse"), ws_ptr, ws_bytes, _stream())
     _check("heart_block_sparse_attn", rc)
     return out
+
+
+def heart_ubench_mfma_bf16(a, b, n_workgroups: int, iters: int, sink=None):
+    """Enqueue the MFMA-only diagnostic loop; returns the FLOPs it performs."""
+    lib = load_library()
+    if a.numel() != 8192 or b.numel() != 8192:
+        raise ValueError("operands must hold 8192 bf16 elements")
+    if sink is None:
+        sink = torch.zeros(1, dtype=torch.float32, device=a.device)
+    rc = lib.heart_ubench_mfma_bf16(_dev(a, torch.bfloat16, "a"), _dev(b, torch.bfloat16, "b"),
+                                    int(n_workgroups), int(iters), _dev(sink, torch.float32, "sink"),
+                                    _stream())
+    _check("heart_ubench_mfma_bf16", rc)
+    return float(n_workgroups) * 4 * iters * 16 * 32768
+
+
+def heart_ubench_copy(src, dst):
+    """Enqueue a plain device copy src -> dst; returns the HBM bytes it moves (read + write)."""
+    lib = load_library()
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("src and dst must have the same size")
+    rc = lib.heart_ubench_copy(_dev(src, src.dtype, "src"), _dev(dst, dst.dtype, "dst"), nbytes, _stream())
+    _check("heart_ubench_copy", rc)
+    return 2.0 * nbytes

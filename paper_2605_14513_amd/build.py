@@ -9,7 +9,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libheart.so")
-SOURCES = ["heart_api.hip", "pool_qk.hip", "drift.hip", "mask_topp.hip", "block_sparse_attn.hip"]
+SOURCES = ["heart_api.hip", "pool_qk.hip", "drift.hip", "mask_topp.hip", "block_sparse_attn.hip",
+           "ubench.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",

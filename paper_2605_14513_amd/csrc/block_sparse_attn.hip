@@ -92,28 +92,36 @@ constexpr int kOrderClasses = 32; // count classes of the work-order sort
 // block) items, longest kept list first.  Stable counting sort by count class
 // (class 0 = the longest rows) in one workgroup: thread t owns a contiguous segment of
 // the items and one column of the class histogram, so that items of a class keep
-// their natural order.
+// their natural order.  The counts are first read once, coalesced and all in flight
+// (they were written by another kernel and come from memory, so dependent rounds of
+// strided reads would cost microseconds each), and kept as class bytes in LDS when
+// they fit (kStaged); otherwise the segments are read from global memory.
+constexpr int kOrderStagedMax = 96 * 1024;  // items whose classes fit next to the histogram
+template <bool kStaged>
 __global__ __launch_bounds__(256) void attn_order_kernel(const int *__restrict__ kept_count, int n,
-                                                         int Nb, int *__restrict__ order) {
+                                                         int Nb, uint32_t mult,
+                                                         int *__restrict__ order) {
   __shared__ int hist[kOrderClasses][256];
   __shared__ int scan[256];
+  extern __shared__ unsigned char cls_lds[];  // [n] when kStaged
   const int t = threadIdx.x;
   const int per = (n + 255) / 256;
   const int i0 = min(n, t * per), i1 = min(n, i0 + per);
+  // class of a count c in [0, Nb]: (kOrderClasses-1) - floor(c * mult / 2^16) with
+  // mult = floor((kOrderClasses-1) * 2^16 / Nb) from the host (no integer division here)
   auto cls = [&](int c) -> int {
     c = min(max(c, 0), Nb);
-    return (kOrderClasses - 1) - (int)(((long long)c * (kOrderClasses - 1)) / Nb);
+    return (kOrderClasses - 1) - (int)(((uint32_t)c * mult) >> 16);
   };
+  auto cls_of = [&](int i) -> int { return kStaged ? (int)cls_lds[i] : cls(kept_count[i]); };
 #pragma unroll
   for (int b = 0; b < kOrderClasses; ++b) hist[b][t] = 0;
-  for (int i = i0; i < i1; i += 8) {
-    int c[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) c[e] = i + e < i1 ? kept_count[i + e] : 0;
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-      if (i + e < i1) hist[cls(c[e])][t] += 1;
+  if (kStaged) {
+#pragma unroll 16
+    for (int i = t; i < n; i += 256) cls_lds[i] = (unsigned char)cls(kept_count[i]);
+    __syncthreads();
   }
+  for (int i = i0; i < i1; ++i) hist[cls_of(i)][t] += 1;
   __syncthreads();
   // exclusive scan over the histogram flattened class-major (index = class * 256 + thread)
   int *flat = &hist[0][0];
@@ -134,22 +142,16 @@ __global__ __launch_bounds__(256) void attn_order_kernel(const int *__restrict__
     run += x;
   }
   __syncthreads();
-  for (int i = i0; i < i1; i += 8) {
-    int c[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) c[e] = i + e < i1 ? kept_count[i + e] : 0;
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-      if (i + e < i1) {
-        const int b = cls(c[e]);
-        const int pos = hist[b][t];
-        hist[b][t] = pos + 1;
-        order[pos] = i + e;
-      }
+  for (int i = i0; i < i1; ++i) {
+    const int b = cls_of(i);
+    const int pos = hist[b][t];
+    hist[b][t] = pos + 1;
+    order[pos] = i;
   }
 }
+
 #ifndef HEART_ATTN_PF
-#define HEART_ATTN_PF 4
+#define HEART_ATTN_PF 4  // LDS fragment reads in flight ahead of the MFMAs
 #endif
 #ifndef HEART_ATTN_OCC
 #define HEART_ATTN_OCC 2  // waves per SIMD the register budget is sized for
@@ -660,8 +662,24 @@ static int launch_attn_t(const heart_shape &s, const void *q, const void *k, con
                                : (long long)BH * ((Nb + kNumXcd - 1) / kNumXcd) * kNumXcd;
   if (grid > 0x7fffffffLL) return fail(HEART_EUNSUPPORTED, "heart_block_sparse_attn: grid too large");
   if (order) {
-    hipLaunchKernelGGL(attn_order_kernel, dim3(1), dim3(256), 0, st, kept_count, (int)n_items, Nb,
-                       order);
+    const uint32_t mult = (uint32_t)(((kOrderClasses - 1) << 16) / Nb);
+    if (n_items <= kOrderStagedMax) {
+      auto okern = attn_order_kernel<true>;
+      static bool order_attr_set = false;
+      if (!order_attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(okern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           kOrderStagedMax);
+        if (e != hipSuccess)
+          return fail(HEART_EHIP, "hipFuncSetAttribute(order kernel LDS): %s", hipGetErrorString(e));
+        order_attr_set = true;
+      }
+      hipLaunchKernelGGL(okern, dim3(1), dim3(256), (size_t)((n_items + 15) / 16 * 16), st,
+                         kept_count, (int)n_items, Nb, mult, order);
+    } else {
+      hipLaunchKernelGGL(attn_order_kernel<false>, dim3(1), dim3(256), 0, st, kept_count,
+                         (int)n_items, Nb, mult, order);
+    }
     if (int rc = check_launch("attn_order_kernel")) return rc;
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(BLK * 2), lds, st,

@@ -153,4 +153,24 @@ size_t heart_attn_workspace_bytes(const heart_shape *s) {
   return (size_t)s->B * s->H * nb * sizeof(int);
 }
 
+int heart_ubench_mfma_bf16(const void *a_bf16, const void *b_bf16, int n_workgroups, int iters,
+                           float *sink, void *stream) {
+  clear_error();
+  if (!a_bf16 || !b_bf16 || !sink) return fail(HEART_EINVAL, "heart_ubench_mfma_bf16: NULL pointer argument");
+  if (!aligned16(a_bf16) || !aligned16(b_bf16))
+    return fail(HEART_EUNSUPPORTED, "heart_ubench_mfma_bf16: operands must be 16-byte aligned");
+  if (n_workgroups <= 0 || iters <= 0 || n_workgroups > (1 << 20) || iters > (1 << 24))
+    return fail(HEART_EINVAL, "heart_ubench_mfma_bf16: n_workgroups in [1, 2^20], iters in [1, 2^24]");
+  return launch_ubench_mfma(a_bf16, b_bf16, n_workgroups, iters, sink, (hipStream_t)stream);
+}
+
+int heart_ubench_copy(const void *src, void *dst, size_t bytes, void *stream) {
+  clear_error();
+  if (!src || !dst) return fail(HEART_EINVAL, "heart_ubench_copy: NULL pointer argument");
+  if (!aligned16(src) || !aligned16(dst) || bytes % 16 != 0 || bytes == 0)
+    return fail(HEART_EUNSUPPORTED,
+                "heart_ubench_copy: pointers 16-byte aligned, bytes a positive multiple of 16");
+  return launch_ubench_copy(src, dst, bytes, (hipStream_t)stream);
+}
+
 }  // extern "C"

@@ -125,4 +125,8 @@ int launch_attn(const heart_shape &s, const void *q, const void *k, const void *
                 const int *kept_idx, const int *kept_count, float scale, void *out, float *lse,
                 int *order, hipStream_t st);
 
+int launch_ubench_mfma(const void *a, const void *b, int n_wg, int iters, float *sink,
+                       hipStream_t st);
+int launch_ubench_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
+
 }  // namespace heart

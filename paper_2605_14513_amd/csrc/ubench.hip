@@ -1,0 +1,70 @@
+// Diagnostic kernels that measure what the chip sustains, for the roofline accounting of
+// the benchmark: the bf16 matrix-core rate on given operand data, and a plain copy.
+// MI355X is power limited: the sustained clock, and with it the matrix-core rate,
+// depends on the bits that flow through the MFMA units (all-zero operands run at the
+// nominal clock, normally distributed ones about 30 % slower), so the attainable
+// ceiling of a bf16 kernel has to be measured on data like its own.
+#include "heart_internal.h"
+
+namespace heart {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 ub_bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float ub_f32x16_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t ub_u32x4_t;
+
+// Every wavefront keeps 4 A and 4 B fragments (read once from the 8192-element operand
+// arrays) and 4 independent accumulators in registers and issues 16 * iters
+// v_mfma_f32_32x32x16_bf16; two workgroups of four wavefronts fit a CU.
+__global__ __launch_bounds__(256, 2) void ubench_mfma_kernel(const ub_u32x4_t *__restrict__ a,
+                                                             const ub_u32x4_t *__restrict__ b,
+                                                             int iters, float *sink) {
+  ub_u32x4_t av[4], bv[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    av[i] = a[(threadIdx.x + 64 * i) % 1024];
+    bv[i] = b[(threadIdx.x * 3 + 64 * i) % 1024];
+  }
+  ub_f32x16_t acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+            __builtin_bit_cast(ub_bf16x8_t, av[(i + u) % 4]), __builtin_bit_cast(ub_bf16x8_t, bv[i]),
+            acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[i][r];
+  // keeps the accumulators alive; the comparison is practically never true
+  if (s == 12345.678f) sink[0] = s;
+}
+
+__global__ __launch_bounds__(256) void ubench_copy_kernel(const ub_u32x4_t *__restrict__ src,
+                                                          ub_u32x4_t *__restrict__ dst, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+    dst[i] = __builtin_nontemporal_load(src + i);
+}
+
+int launch_ubench_mfma(const void *a, const void *b, int n_wg, int iters, float *sink,
+                       hipStream_t st) {
+  hipLaunchKernelGGL(ubench_mfma_kernel, dim3((unsigned)n_wg), dim3(256), 0, st,
+                     (const ub_u32x4_t *)a, (const ub_u32x4_t *)b, iters, sink);
+  return check_launch("ubench_mfma_kernel");
+}
+
+int launch_ubench_copy(const void *src, void *dst, size_t bytes, hipStream_t st) {
+  hipLaunchKernelGGL(ubench_copy_kernel, dim3(256 * 16), dim3(256), 0, st,
+                     (const ub_u32x4_t *)src, (ub_u32x4_t *)dst, bytes / 16);
+  return check_launch("ubench_copy_kernel");
+}
+
+}  // namespace heart

@@ -347,7 +347,8 @@ def test_attn_launch_order_is_a_stable_longest_first_permutation(heart):
     assert (order[n:] == -7).all()  # nothing written past the stated size
     order = order[:n]
     assert np.array_equal(np.sort(order), np.arange(n))
-    classes = 31 - (cnt.reshape(-1).astype(np.int64) * 31) // Nb
+    mult = (31 << 16) // Nb
+    classes = 31 - ((cnt.reshape(-1).astype(np.int64) * mult) >> 16)
     want = np.argsort(classes, kind="stable")
     assert np.array_equal(order, want)
     assert torch.equal(out_ordered, out_natural)
