@@ -19,20 +19,20 @@
 // keys of its query per MFMA, and any assignment of keys to the 8 slots is valid
 // as long as the A operand (V^T) uses the same one.
 //
-// LDS holds one K tile [block][D+8] bf16 (16-byte fragment reads of 16 consecutive
-// key rows hit 16 distinct 4-bank groups) and one V^T tile [D][block+8] bf16.
-// Within every group of 16 keys the V^T tile stores the 4-key chunks in the order
-// 0,2,1,3: the 8 keys a lane needs for one MFMA (chunks {0,2} for lanes 0-31,
-// {1,3} for lanes 32-63) are then one aligned 16-byte read.  V is transposed in
-// registers on its way from global memory (4 keys x 8 d per lane, byte permutes).
+// K and V never pass through registers on their way in: they are copied from global
+// memory straight into LDS by 16-byte LDS-direct buffer loads (rows past the end of the
+// sequence are out of range for the buffer descriptor and arrive as zeros, with no
+// branch and no address clamping).  Both tiles stay row-major [key][d] and unpadded (a
+// direct load fills 1 KB of consecutive LDS); the 16-byte chunk index is XOR-swizzled
+// with the row so that fragment reads are bank-conflict free.  K fragments are plain
+// 16-byte reads; V^T fragments come from the transposing LDS read ds_read_b64_tr_b16.
 //
-// Pipeline per kept key block (two workgroup barriers):
-//   top      K of the next block -> registers (buffer loads in flight during the MFMAs)
-//   slices   the block is consumed in 64-key slices: S^T, online softmax, O^T update
-//   barrier A (after the last S^T): K registers -> LDS; V of the next block -> registers
-//   barrier B (after the last O^T update): V registers -> transposed -> LDS
-// Global loads are buffer loads: rows past the end of the sequence are out of range
-// for the descriptor and read as zero, with no branch and no address clamping.
+// The kept key blocks are consumed as one stream of 32-key slices.  K and V arrive in
+// double-buffered stages of 64 rows, loaded two slices ahead; V stages are skewed by one
+// slice against K stages so that one workgroup barrier per 64 keys retires both (see
+// the comment at the loop).  The softmax scale and log2(e) are folded into Q once, and
+// the S^T accumulators start from minus the running reference exponent, so an
+// accumulator goes into the exponential as it is.
 //
 // Workgroup ids are remapped (they are dealt round-robin to the 8 XCDs, each with its
 // own L2).  With a work-order list (attn_order_kernel, when the caller passes a
@@ -85,7 +85,10 @@ __device__ __forceinline__ u32x4_t head_rsrc_words(const uint16_t *base, uint32_
 
 constexpr int kNumXcd = 8;
 constexpr int kStageRows = 64;    // key rows per K / V stage buffer (two 32-key slices)
-constexpr int kOrderRun = 8;      // consecutive work-list entries that go to one XCD
+#ifndef HEART_ORDER_RUN
+#define HEART_ORDER_RUN 8
+#endif
+constexpr int kOrderRun = HEART_ORDER_RUN;  // consecutive work-list entries that go to one XCD
 constexpr int kOrderClasses = 32; // count classes of the work-order sort
 
 // Work order for the attention launch: a permutation of the n = B*H*Nb (head, query
