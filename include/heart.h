@@ -137,11 +137,12 @@ int heart_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float 
  * lse: fp32 [B,H,N] natural-log-sum-exp of the scaled logits over the kept keys,
  * or NULL.  A row with kept_count == 0 yields zeros (lse = -inf).
  * workspace: device memory of at least heart_attn_workspace_bytes(shape) bytes, 16-byte
- * aligned, or NULL.  With a workspace the call first builds a launch order in it
- * (query blocks with the longest kept lists start first, which removes most of the
- * idle tail when kept counts differ between rows); the results are the same with and
- * without it.  The contents need not be preserved between calls; two calls that run
- * concurrently must not share a workspace.
+ * aligned, or NULL.  With a workspace the call first builds a launch plan in it (whole
+ * heads are assigned to the XCDs so that the workgroups of an XCD share one head's K/V
+ * in its L2; inside a head the query blocks with the longest kept lists start first;
+ * workgroups take items with atomic counters, which levels the load).  The results are
+ * the same with and without it.  The contents need not be preserved between calls; two
+ * calls that run concurrently must not share a workspace.
  */
 int heart_block_sparse_attn(const heart_shape *shape, const void *q_bf16, const void *k_bf16,
                             const void *v_bf16, const int *kept_idx, const int *kept_count,

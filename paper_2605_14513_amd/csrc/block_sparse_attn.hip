@@ -34,14 +34,19 @@
 // the S^T accumulators start from minus the running reference exponent, so an
 // accumulator goes into the exponential as it is.
 //
-// Workgroup ids are remapped (they are dealt round-robin to the 8 XCDs, each with its
-// own L2).  With a work-order list (attn_order_kernel, when the caller passes a
-// workspace) the query blocks are launched longest first: kept counts range from 1 to
-// Nb per row, and a long row that starts late would otherwise leave most of the chip
-// idle at the end.  The order is a stable counting sort on 32 count classes, so rows of
-// a class keep their natural order (same head, neighbouring query blocks, which share
-// kept K/V blocks), and runs of 8 consecutive list entries go to the same XCD.  Without
-// a list an XCD works on a contiguous eighth of the query blocks of every head.
+// Scheduling.  Kept counts range from 1 to Nb per row and the densities of the heads
+// differ a lot, the K/V of one head (16.8 MB at N = 32760, D = 128) is far larger than
+// the 4 MB L2 of an XCD, and every query block re-reads its kept K/V blocks.  With a
+// caller-provided workspace the launch therefore follows a plan (attn_plan_kernel,
+// attn_order_kernel): whole heads are assigned to the 8 XCDs (greedily, heaviest head
+// first, by total kept count), each XCD walks through its heads one at a time -- all
+// its workgroups then share one head's K/V through that XCD's L2, and only 8 heads are
+// in flight in the memory-side cache -- and inside a head the rows with the longest
+// kept lists start first (stable counting sort on 32 count classes), so that no long
+// row starts late.  A workgroup takes the next item of its XCD's list with an atomic
+// counter; when that list is exhausted it takes from another XCD's list, which levels
+// whatever imbalance the head assignment left.  Without a workspace an XCD works on a
+// contiguous eighth of the query blocks of every head, in index order.
 #include "heart_internal.h"
 
 namespace heart {
@@ -85,35 +90,95 @@ __device__ __forceinline__ u32x4_t head_rsrc_words(const uint16_t *base, uint32_
 
 constexpr int kNumXcd = 8;
 constexpr int kStageRows = 64;    // key rows per K / V stage buffer (two 32-key slices)
-#ifndef HEART_ORDER_RUN
-#define HEART_ORDER_RUN 8
-#endif
-constexpr int kOrderRun = HEART_ORDER_RUN;  // consecutive work-list entries that go to one XCD
-constexpr int kOrderClasses = 32; // count classes of the work-order sort
+constexpr int kOrderClasses = 32;   // count classes of the per-head sort
+constexpr int kPlanHdr = 24;        // plan header: 8 cursors, 8 list lengths, 8 list offsets
+constexpr int kPlanMaxHeads = 1024; // beyond this heads are dealt to the XCDs round-robin
+// Plan layout (ints): [0,8) cursors, [8,16) items per XCD list, [16,24) offset of each
+// list in seq, [24, 24+BH) offset of each head's items in seq, then seq[BH*Nb]: the
+// concatenated XCD lists of item ids (item = (b*H + h) * Nb + query block).
 
-// Work order for the attention launch: a permutation of the n = B*H*Nb (head, query
-// block) items, longest kept list first.  Stable counting sort by count class
-// (class 0 = the longest rows) in one workgroup: thread t owns a contiguous segment of
-// the items and one column of the class histogram, so that items of a class keep
-// their natural order.  The counts are first read once, coalesced and all in flight
-// (they were written by another kernel and come from memory, so dependent rounds of
-// strided reads would cost microseconds each), and kept as class bytes in LDS when
-// they fit (kStaged); otherwise the segments are read from global memory.
-// Heads are sorted in groups: the launch then walks through the heads group by group, so
-// that the K/V of the heads in flight stay within the 256 MB memory-side cache, while
-// inside a group the long rows still start first.  A group holds about 128 MB of K/V
-// (8 heads at N = 32760, D = 128; measured optimum 6 to 13 heads there).
-constexpr long long kOrderGroupBytes = 128ll << 20;
+// One workgroup: total kept count per head, heads ranked by it, greedy assignment of
+// heads (heaviest first) to the least loaded XCD, list offsets, cursors reset.
+__global__ __launch_bounds__(256) void attn_plan_kernel(const int *__restrict__ kept_count, int BH,
+                                                        int Nb, int *__restrict__ plan) {
+  __shared__ int w_head[kPlanMaxHeads];
+  __shared__ int sorted[kPlanMaxHeads];
+  __shared__ int xcd_of[kPlanMaxHeads], rank_of[kPlanMaxHeads];
+  __shared__ int n_heads[kNumXcd], off[kNumXcd];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  if (BH <= kPlanMaxHeads) {
+    for (int bh = wave; bh < BH; bh += 4) {
+      int s = 0;
+      for (int i = lane; i < Nb; i += 64) s += min(max(kept_count[(size_t)bh * Nb + i], 0), Nb);
+      s = wave_sum_i32(s);
+      if (lane == 0) w_head[bh] = s;
+    }
+    __syncthreads();
+    // rank by (work descending, index ascending)
+    for (int bh = t; bh < BH; bh += 256) {
+      const int w = w_head[bh];
+      int r = 0;
+      for (int j = 0; j < BH; ++j) {
+        const int wj = w_head[j];
+        r += (wj > w) || (wj == w && j < bh);
+      }
+      sorted[r] = bh;
+    }
+    __syncthreads();
+    if (t == 0) {
+      long long load[kNumXcd];
+      int nh[kNumXcd];
+      for (int x = 0; x < kNumXcd; ++x) load[x] = 0, nh[x] = 0;
+      for (int r = 0; r < BH; ++r) {
+        const int bh = sorted[r];
+        int best = 0;
+        for (int x = 1; x < kNumXcd; ++x)
+          if (load[x] < load[best]) best = x;
+        xcd_of[bh] = best;
+        rank_of[bh] = nh[best]++;
+        load[best] += w_head[bh] + Nb;  // (+Nb: a row costs about one key block of fixed work)
+      }
+      for (int x = 0; x < kNumXcd; ++x) n_heads[x] = nh[x];
+    }
+  } else {
+    if (t < kNumXcd) n_heads[t] = BH / kNumXcd + (t < BH % kNumXcd ? 1 : 0);
+  }
+  __syncthreads();
+  if (t == 0) {
+    int run = 0;
+    for (int x = 0; x < kNumXcd; ++x) {
+      off[x] = run;
+      run += n_heads[x] * Nb;
+    }
+  }
+  __syncthreads();
+  if (t < kNumXcd) {
+    plan[t] = 0;
+    plan[kNumXcd + t] = n_heads[t] * Nb;
+    plan[2 * kNumXcd + t] = off[t];
+  }
+  for (int bh = t; bh < BH; bh += 256) {
+    const int x = BH <= kPlanMaxHeads ? xcd_of[bh] : bh % kNumXcd;
+    const int r = BH <= kPlanMaxHeads ? rank_of[bh] : bh / kNumXcd;
+    plan[kPlanHdr + bh] = off[x] + r * Nb;
+  }
+}
+
+// One workgroup per head: the Nb items of the head, longest kept list first, into the
+// head's range of seq.  Stable counting sort by count class (class 0 = the longest
+// rows): thread t owns a contiguous segment of the items and one column of the class
+// histogram, so that items of a class keep their natural order.  The counts are first
+// read once, coalesced and all in flight, and kept as class bytes in LDS when they fit
+// (kStaged); otherwise the segments are read from global memory.
 constexpr int kOrderStagedMax = 96 * 1024;  // items whose classes fit next to the histogram
 template <bool kStaged>
-__global__ __launch_bounds__(256) void attn_order_kernel(const int *__restrict__ kept_count,
-                                                         int n_all, int seg, int Nb, uint32_t mult,
-                                                         int *__restrict__ order) {
-  // workgroup g sorts the items [g * seg, min(n_all, (g + 1) * seg)) into the same range
-  const int seg0 = blockIdx.x * seg;
-  const int n = min(seg, n_all - seg0);
-  kept_count += seg0;
-  order += seg0;
+__global__ __launch_bounds__(256) void attn_order_kernel(const int *__restrict__ kept_count, int BH,
+                                                         int Nb, uint32_t mult,
+                                                         int *__restrict__ plan) {
+  const int n = Nb;
+  const int item0 = blockIdx.x * Nb;
+  kept_count += item0;
+  int *order = plan + kPlanHdr + BH + plan[kPlanHdr + blockIdx.x];
   __shared__ int hist[kOrderClasses][256];
   __shared__ int scan[256];
   extern __shared__ unsigned char cls_lds[];  // [n] when kStaged
@@ -159,7 +224,7 @@ __global__ __launch_bounds__(256) void attn_order_kernel(const int *__restrict__
     const int b = cls_of(i);
     const int pos = hist[b][t];
     hist[b][t] = pos + 1;
-    order[pos] = seg0 + i;
+    order[pos] = item0 + i;
   }
 }
 
@@ -177,7 +242,7 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
     long long qsn, long long ksb, long long ksh, long long ksn, long long vsb, long long vsh,
     long long vsn, long long osb, long long osh, long long osn, int H, int BH, int N, int Nb,
     const int *__restrict__ kept_idx, const int *__restrict__ kept_count, float scale_log2e,
-    float *__restrict__ lse, const int *__restrict__ order, int n_items) {
+    float *__restrict__ lse, int *__restrict__ plan) {
   constexpr int NT = BLK * 2;            // threads
   constexpr int NW = NT / 64;            // wavefronts
   constexpr int DT = D / 32;             // 32-wide d tiles of the output
@@ -197,35 +262,16 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   extern __shared__ __align__(1024) unsigned char smem[];
   const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)smem;
 
-  // ---- workgroup id -> (head, query block), XCD-aware ------------------------------
-  int bh, qb;
-  if (order) {
-    // list position: runs of kOrderRun consecutive entries per XCD, XCDs interleaved
-    const int xcd = (int)(blockIdx.x % kNumXcd);
-    const long long slot = blockIdx.x / kNumXcd;
-    const long long pos =
-        (slot / kOrderRun) * (kNumXcd * kOrderRun) + xcd * kOrderRun + slot % kOrderRun;
-    if (pos >= n_items) return;  // padding (whole workgroup, before any barrier)
-    const int item = min(max(order[pos], 0), n_items - 1);
-    bh = item / Nb;
-    qb = item % Nb;
-  } else {
-    const int per = (Nb + kNumXcd - 1) / kNumXcd;  // query blocks per XCD and head
-    const int xcd = (int)(blockIdx.x % kNumXcd);
-    const long long slot = blockIdx.x / kNumXcd;
-    bh = (int)(slot / per);
-    qb = xcd * per + (int)(slot % per);
-    if (qb >= Nb) return;  // padding of the last eighth (whole workgroup, before any barrier)
-  }
-  const int b = bh / H, h = bh % H;
   const int t = threadIdx.x;
   const int lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int l32 = lane & 31, hf = lane >> 5;
 
-  const __amdgpu_buffer_rsrc_t q_rs = head_rsrc(q + b * qsb + h * qsh, (uint32_t)(N * qsn * 2));
-  const u32x4_t k_rs = head_rsrc_words(k + b * ksb + h * ksh, (uint32_t)(N * ksn * 2));
-  const u32x4_t v_rs = head_rsrc_words(v + b * vsb + h * vsh, (uint32_t)(N * vsn * 2));
+  // ---- state of the item (head, query block) being processed; set by begin_item ---------
+  int bh = 0, qb = 0, b = 0, h = 0, qrow = 0, cnt = 0;
+  const int *idx = kept_idx;
+  __amdgpu_buffer_rsrc_t q_rs = head_rsrc(q, 0);
+  u32x4_t k_rs = head_rsrc_words(k, 0), v_rs = head_rsrc_words(v, 0);
   const uint32_t k_row_bytes = (uint32_t)ksn * 2u, v_row_bytes = (uint32_t)vsn * 2u;
 
   // ---- per-lane constants of the LDS layout ---------------------------------------------
@@ -290,10 +336,22 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
                    :: "s"(dst), "v"(voffset), "s"(k_rs) : "memory");
   };
 
-  // ---- Q fragments (B operand of S^T = K Q^T), kept in registers ----------------
-  const int qrow = qb * BLK + wave * 32 + l32;
-  Frag8 qf[KS];
-  {
+  Frag8 qf[KS];      // Q fragments (B operand of S^T = K Q^T), kept in registers
+  f32x16_t o[DT];    // O^T accumulators
+  float m_ref = 0.f; // reference exponent (log2 domain) of the running sums
+  // S^T accumulators start from -m_ref instead of zero, so they hold logits relative to
+  // the reference exponent and go into the exponential as they are
+  f32x16_t cinit;
+  float l_run = 0.f;  // running sum over this lane's keys, relative to m_ref
+  auto begin_item = [&](int item) __attribute__((always_inline)) {
+    bh = item / Nb;
+    qb = item % Nb;
+    b = bh / H;
+    h = bh % H;
+    q_rs = head_rsrc(q + b * qsb + h * qsh, (uint32_t)(N * qsn * 2));
+    k_rs = head_rsrc_words(k + b * ksb + h * ksh, (uint32_t)(N * ksn * 2));
+    v_rs = head_rsrc_words(v + b * vsb + h * vsh, (uint32_t)(N * vsn * 2));
+    qrow = qb * BLK + wave * 32 + l32;
     const uint32_t q_off = (uint32_t)qrow * ((uint32_t)qsn * 2u) + (uint32_t)hf * 16u;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
@@ -305,24 +363,19 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
 #pragma unroll
       for (int w = 0; w < 4; ++w)
         qf[ks].u[w] = cvt_pk_bf16(bf16lo(qf[ks].u[w]) * scale_log2e, bf16hi(qf[ks].u[w]) * scale_log2e);
-  }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
+    m_ref = -__builtin_inff();
+#pragma unroll
+    for (int r = 0; r < 16; ++r) cinit[r] = 0.f;
+    l_run = 0.f;
+    const size_t row = (size_t)bh * Nb + qb;
+    cnt = min(kept_count[row], Nb);
+    idx = kept_idx + row * Nb;
+  };
 
-  f32x16_t o[DT];
-#pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
-  float m_ref = -__builtin_inff();  // reference exponent (log2 domain) of the running sums
-  // S^T accumulators start from -m_ref instead of zero, so they hold logits relative to
-  // the reference exponent and go into the exponential as they are
-  f32x16_t cinit;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) cinit[r] = 0.f;
-  float l_run = 0.f;  // running sum over this lane's keys, relative to m_ref
-
-  const size_t row = (size_t)bh * Nb + qb;
-  const int cnt = min(kept_count[row], Nb);
-  const int *idx = kept_idx + row * Nb;
   // The kept blocks are consumed as one sequence of 32-key slices.  Kept indices are
   // clamped into [0, Nb) so that a bad list cannot leave the tensors; entries past the
   // end of the list repeat the last one (their data is never used).
@@ -511,6 +564,47 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
     __syncthreads();
   };
 
+  // ---- work loop --------------------------------------------------------------------------
+  // With a plan the workgroups are persistent (two per CU): each takes items from the list
+  // of its XCD (workgroup ids are dealt round-robin to the XCDs) with an atomic cursor and,
+  // once that list is empty, from the other XCDs' lists.  Without a plan a workgroup
+  // processes the one item its id maps to.
+  __shared__ int s_item;
+  const int x0 = (int)(blockIdx.x % kNumXcd);
+  const int len0 = plan ? plan[kNumXcd + x0] : 0;
+  const int off0 = plan ? plan[2 * kNumXcd + x0] : 0;
+  // (thread 0) item for cursor value i_own of the own list, else from another list, else -1
+  auto take = [&](int i_own) -> int {
+    if (i_own >= 0 && i_own < len0) return plan[kPlanHdr + BH + off0 + i_own];
+    for (int k2 = 1; k2 < kNumXcd; ++k2) {
+      const int x = (x0 + k2) % kNumXcd;
+      const int len = plan[kNumXcd + x];
+      if (len <= 0) continue;
+      const int i = atomicAdd(&plan[x], 1);
+      if (i < len) return plan[kPlanHdr + BH + plan[2 * kNumXcd + x] + i];
+    }
+    return -1;
+  };
+  int item = -1;
+  if (plan) {
+    if (t == 0) s_item = take(len0 > 0 ? atomicAdd(&plan[x0], 1) : -1);
+    __syncthreads();
+    item = __builtin_amdgcn_readfirstlane(s_item);
+  } else {
+    // XCD x takes the x-th eighth of the query blocks of every head, heads in order
+    const int per = (Nb + kNumXcd - 1) / kNumXcd;  // query blocks per XCD and head
+    const long long slot = blockIdx.x / kNumXcd;
+    const int qb0 = x0 * per + (int)(slot % per);
+    if (qb0 < Nb) item = (int)(slot / per) * Nb + qb0;  // else: padding of the last eighth
+  }
+  while (item >= 0 && item < BH * Nb) {
+  begin_item(item);
+  // (thread 0) cursor value and item id of the NEXT item.  The cursor is advanced only in
+  // the last loop body, not earlier: items are then started in list order up to about a
+  // microsecond, and neighbouring rows of a head, whose kept lists overlap, walk through
+  // K/V together (reserving the next item a whole row ahead costs a third of the L2 hits).
+  int i_next = -1, item_next = -1;
+
   if (cnt > 0) {
     // ---- prologue: stages 0 and 1 in flight, S^T and maximum of slice 0 --------------------
     {
@@ -561,6 +655,7 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
       wait_loads_and_barrier();
 #pragma unroll
       for (int i = 0; i < EPB; ++i) asm volatile("" : "+s"(jn[i]));  // loaded before the barrier
+      if (plan && t == 0 && st + 2 >= T && len0 > 0) i_next = atomicAdd(&plan[x0], 1);
       refill(G_B0);
       // ---- slice s0+1; stage st+2 -> buffers 0 ----
       {
@@ -618,6 +713,10 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
     // loads of stages past the end may still be in flight towards LDS
     wait_loads_and_barrier();
   }
+  if (plan && t == 0) {
+    if (i_next < 0 && len0 > 0) i_next = atomicAdd(&plan[x0], 1);  // (row without kept blocks)
+    if (i_next >= 0 && i_next < len0) item_next = plan[kPlanHdr + BH + off0 + i_next];
+  }
 
   // ---- epilogue: normalise, stage through LDS, coalesced bf16 store -----------------------
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -648,6 +747,11 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
       *reinterpret_cast<u32x4_t *>(obase + (long long)n * osn + o_c) =
           *reinterpret_cast<const u32x4_t *>(sO + r * SO + o_c);
   }
+  if (!plan) break;
+  if (t == 0) s_item = item_next >= 0 ? item_next : take(-1);
+  __syncthreads();  // also: everyone has read the output staging before the next item's loads
+  item = __builtin_amdgcn_readfirstlane(s_item);
+  }  // work loop
 }
 
 template <int D, int BLK>
@@ -670,18 +774,27 @@ static int launch_attn_t(const heart_shape &s, const void *q, const void *k, con
   const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
   const float scale_log2e = sc * 1.4426950408889634f;
   const long long n_items = (long long)BH * Nb;
-  constexpr long long kGroup = kNumXcd * kOrderRun;
-  const long long grid = order ? (n_items + kGroup - 1) / kGroup * kGroup
-                               : (long long)BH * ((Nb + kNumXcd - 1) / kNumXcd) * kNumXcd;
+  long long grid = (long long)BH * ((Nb + kNumXcd - 1) / kNumXcd) * kNumXcd;
+  if (order) {
+    // persistent workgroups: as many as are resident at once (HEART_ATTN_OCC per SIMD, i.e.
+    // two workgroups of four wavefronts per CU)
+    static int n_cu = 0;  // of the device that was current at the first call
+    if (n_cu == 0) {
+      int dev = 0, v = 0;
+      if (hipGetDevice(&dev) != hipSuccess ||
+          hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+        return fail(HEART_EHIP, "heart_block_sparse_attn: cannot query the number of CUs");
+      n_cu = v;
+    }
+    const long long resident = (long long)n_cu * HEART_ATTN_OCC * 4 / (BLK / 32);
+    grid = n_items < resident ? n_items : resident;
+  }
   if (grid > 0x7fffffffLL) return fail(HEART_EUNSUPPORTED, "heart_block_sparse_attn: grid too large");
   if (order) {
+    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(256), 0, st, kept_count, BH, Nb, order);
+    if (int rc = check_launch("attn_plan_kernel")) return rc;
     const uint32_t mult = (uint32_t)(((kOrderClasses - 1) << 16) / Nb);
-    // one sorted segment per group of heads (see kOrderGroupBytes)
-    const long long kv_bytes_per_head = 4ll * s.N * D;
-    const long long group_heads = kOrderGroupBytes / kv_bytes_per_head > 1 ? kOrderGroupBytes / kv_bytes_per_head : 1;
-    const long long seg = group_heads * Nb;
-    const unsigned n_seg = (unsigned)((n_items + seg - 1) / seg);
-    if (seg <= kOrderStagedMax) {
+    if (Nb <= kOrderStagedMax) {
       auto okern = attn_order_kernel<true>;
       static bool order_attr_set = false;
       if (!order_attr_set) {
@@ -692,11 +805,11 @@ static int launch_attn_t(const heart_shape &s, const void *q, const void *k, con
           return fail(HEART_EHIP, "hipFuncSetAttribute(order kernel LDS): %s", hipGetErrorString(e));
         order_attr_set = true;
       }
-      hipLaunchKernelGGL(okern, dim3(n_seg), dim3(256), (size_t)((seg + 15) / 16 * 16), st,
-                         kept_count, (int)n_items, (int)seg, Nb, mult, order);
+      hipLaunchKernelGGL(okern, dim3((unsigned)BH), dim3(256), (size_t)((Nb + 15) / 16 * 16), st,
+                         kept_count, BH, Nb, mult, order);
     } else {
-      hipLaunchKernelGGL(attn_order_kernel<false>, dim3(n_seg), dim3(256), 0, st, kept_count,
-                         (int)n_items, (int)seg, Nb, mult, order);
+      hipLaunchKernelGGL(attn_order_kernel<false>, dim3((unsigned)BH), dim3(256), 0, st, kept_count,
+                         BH, Nb, mult, order);
     }
     if (int rc = check_launch("attn_order_kernel")) return rc;
   }
@@ -705,7 +818,7 @@ static int launch_attn_t(const heart_shape &s, const void *q, const void *k, con
                      (uint16_t *)out, s.q_stride[0], s.q_stride[1], s.q_stride[2], s.k_stride[0],
                      s.k_stride[1], s.k_stride[2], s.v_stride[0], s.v_stride[1], s.v_stride[2],
                      s.o_stride[0], s.o_stride[1], s.o_stride[2], s.H, BH, s.N, Nb, kept_idx,
-                     kept_count, scale_log2e, lse, (const int *)order, (int)n_items);
+                     kept_count, scale_log2e, lse, order);
   return check_launch("attn_kernel");
 }
 

@@ -12,7 +12,7 @@ import torch
 
 import oracle
 from heart_synth import make_generator
-from heart_testlib import (ATTN_ATOL, assert_lists_equal, assert_means_close,
+from heart_testlib import (check_attn_plan, ATTN_ATOL, assert_lists_equal, assert_means_close,
                            assert_scores_close, gpu, np_gpu, u16)
 
 pytestmark = pytest.mark.gpu
@@ -100,20 +100,10 @@ def test_full_size_path_against_oracle(heart, name):
         assert abs(dens - 0.15) < 0.01
 
     # ---- attention on the oracle's lists: sampled query blocks of sampled heads ---------------
-    n_items = B * H * Nb
-    ws = torch.full((n_items,), -1, dtype=torch.int32, device="cuda")
+    ws = torch.full((heart.heart_attn_workspace_bytes(q0, blk) // 4,), -1, dtype=torch.int32, device="cuda")
     out = heart.heart_block_sparse_attn(q0, k0, v0, blk, np_gpu(oi), np_gpu(oc), workspace=ws)
     torch.cuda.synchronize()
-    # launch order: a permutation; heads in groups of about 128 MB of K/V, inside a group
-    # the count classes in descending length, natural order inside a class
-    order = ws.cpu().numpy()
-    assert np.array_equal(np.sort(order), np.arange(n_items))
-    seg = max(1, (128 << 20) // (4 * N * D)) * Nb
-    mult = (31 << 16) // Nb
-    classes = 31 - ((oc.reshape(-1).astype(np.int64) * mult) >> 16)
-    for s0 in range(0, n_items, seg):
-        want = s0 + np.argsort(classes[s0:s0 + seg], kind="stable")
-        assert np.array_equal(order[s0:s0 + seg], want), f"{name}: launch order of segment at {s0}"
+    check_attn_plan(ws.cpu().numpy(), oc, Nb)
     rng = np.random.default_rng(cfg.seed)
     heads = sorted(set([0, H - 1] + rng.choice(H, size=2, replace=False).tolist()))
     qblocks = sorted(set([0, Nb - 1] + list(range(nt)) + rng.choice(Nb, size=3, replace=False).tolist()))

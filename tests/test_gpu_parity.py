@@ -18,7 +18,7 @@ import torch
 
 import oracle
 from heart_synth import make_generator
-from heart_testlib import (ATTN_ATOL, assert_lists_equal, assert_means_close,
+from heart_testlib import (check_attn_plan, ATTN_ATOL, assert_lists_equal, assert_means_close,
                            assert_scores_close, gpu, np_gpu, u16)
 
 pytestmark = pytest.mark.gpu
@@ -322,15 +322,15 @@ def test_attn_strided_layout_unsorted_lists_and_empty_rows(heart):
     assert err <= ATTN_ATOL, f"max abs err {err:.4f}"
 
 
-def test_attn_launch_order_is_a_stable_longest_first_permutation(heart):
-    # the workspace receives the launch order: a permutation of all (head, query block)
-    # items, sorted by count class (longest first), natural order inside a class; the
-    # output bits do not depend on the order
+def test_attn_launch_plan_and_same_bits_with_and_without_it(heart):
+    # the workspace receives the launch plan (heads assigned to XCDs, rows of a head longest
+    # first); the output bits do not depend on it
     g, st = case("small_ragged")
     cfg = g.cfg
     rng = np.random.default_rng(9)
     Nb = cfg.Nb
     cnt = rng.integers(0, Nb + 1, size=(cfg.B, cfg.H, Nb)).astype(np.int32)
+    cnt[0, 1] //= 3  # heads of different weight
     idx = np.zeros((cfg.B, cfg.H, Nb, Nb), np.int32)
     for b in range(cfg.B):
         for h in range(cfg.H):
@@ -338,22 +338,18 @@ def test_attn_launch_order_is_a_stable_longest_first_permutation(heart):
                 idx[b, h, i, :cnt[b, h, i]] = np.sort(rng.permutation(Nb)[:cnt[b, h, i]])
     q, k, v = gpu(st.q), gpu(st.k), gpu(st.v)
     n = cfg.B * cfg.H * Nb
-    assert heart.heart_attn_workspace_bytes(q, cfg.block) == 4 * n
-    ws = torch.full((n + 3,), -7, dtype=torch.int32, device="cuda")
-    out_ordered = heart.heart_block_sparse_attn(q, k, v, cfg.block, np_gpu(idx), np_gpu(cnt), workspace=ws)
+    words = heart.heart_attn_workspace_bytes(q, cfg.block) // 4
+    assert words == 24 + cfg.B * cfg.H + n
+    ws = torch.full((words + 3,), -7, dtype=torch.int32, device="cuda")
+    out_planned = heart.heart_block_sparse_attn(q, k, v, cfg.block, np_gpu(idx), np_gpu(cnt), workspace=ws)
     out_natural = heart.heart_block_sparse_attn(q, k, v, cfg.block, np_gpu(idx), np_gpu(cnt), workspace=None)
     torch.cuda.synchronize()
-    order = ws.cpu().numpy()
-    assert (order[n:] == -7).all()  # nothing written past the stated size
-    order = order[:n]
-    assert np.array_equal(np.sort(order), np.arange(n))
-    mult = (31 << 16) // Nb
-    classes = 31 - ((cnt.reshape(-1).astype(np.int64) * mult) >> 16)
-    want = np.argsort(classes, kind="stable")
-    assert np.array_equal(order, want)
-    assert torch.equal(out_ordered, out_natural)
+    plan = ws.cpu().numpy()
+    assert (plan[words:] == -7).all()  # nothing written past the stated size
+    check_attn_plan(plan[:words], cnt, Nb)
+    assert torch.equal(out_planned, out_natural)
     with pytest.raises(heart.HeartError):
-        heart.heart_block_sparse_attn(q, k, v, cfg.block, np_gpu(idx), np_gpu(cnt), workspace=ws[:n - 1])
+        heart.heart_block_sparse_attn(q, k, v, cfg.block, np_gpu(idx), np_gpu(cnt), workspace=ws[:words - 1])
 
 
 # ------------------------------------------------------------------------------ P6
