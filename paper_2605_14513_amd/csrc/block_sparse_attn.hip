@@ -37,8 +37,8 @@
 // Scheduling.  Kept counts range from 1 to Nb per row and the densities of the heads
 // differ a lot, the K/V of one head (16.8 MB at N = 32760, D = 128) is far larger than
 // the 4 MB L2 of an XCD, and every query block re-reads its kept K/V blocks.  With a
-// caller-provided workspace the launch therefore follows a plan (attn_plan_kernel,
-// attn_order_kernel): whole heads are assigned to the 8 XCDs (greedily, heaviest head
+// caller-provided workspace the launch therefore follows a plan (attn_order_kernel,
+// attn_plan_kernel): whole heads are assigned to the 8 XCDs (greedily, heaviest head
 // first, by total kept count), each XCD walks through its heads one at a time -- all
 // its workgroups then share one head's K/V through that XCD's L2, and only 8 heads are
 // in flight in the memory-side cache -- and inside a head the rows with the longest
@@ -94,25 +94,22 @@ constexpr int kOrderClasses = 32;   // count classes of the per-head sort
 constexpr int kPlanHdr = 24;        // plan header: 8 cursors, 8 list lengths, 8 list offsets
 constexpr int kPlanMaxHeads = 1024; // beyond this heads are dealt to the XCDs round-robin
 // Plan layout (ints): [0,8) cursors, [8,16) items per XCD list, [16,24) offset of each
-// list in seq, [24, 24+BH) offset of each head's items in seq, then seq[BH*Nb]: the
-// concatenated XCD lists of item ids (item = (b*H + h) * Nb + query block).
+// XCD's heads in the head table, [24, 24+BH) head table (the heads of XCD 0 in the order
+// it walks them, then those of XCD 1, ...), [24+BH, 24+2BH) total kept count per head,
+// then seq[BH*Nb], head-major: seq[head*Nb + p] = the head's p-th item in launch order
+// (item = head * Nb + query block).  Entry i of an XCD's list is item p = i % Nb of its
+// (i / Nb)-th head.
 
-// One workgroup: total kept count per head, heads ranked by it, greedy assignment of
-// heads (heaviest first) to the least loaded XCD, list offsets, cursors reset.
-__global__ __launch_bounds__(256) void attn_plan_kernel(const int *__restrict__ kept_count, int BH,
-                                                        int Nb, int *__restrict__ plan) {
+// One workgroup, after attn_order_kernel: heads ranked by total kept count, greedy
+// assignment of heads (heaviest first) to the least loaded XCD, head table, cursors reset.
+__global__ __launch_bounds__(256) void attn_plan_kernel(int BH, int Nb, int *__restrict__ plan) {
   __shared__ int w_head[kPlanMaxHeads];
   __shared__ int sorted[kPlanMaxHeads];
   __shared__ int xcd_of[kPlanMaxHeads], rank_of[kPlanMaxHeads];
   __shared__ int n_heads[kNumXcd], off[kNumXcd];
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int t = threadIdx.x;
   if (BH <= kPlanMaxHeads) {
-    for (int bh = wave; bh < BH; bh += 4) {
-      int s = 0;
-      for (int i = lane; i < Nb; i += 64) s += min(max(kept_count[(size_t)bh * Nb + i], 0), Nb);
-      s = wave_sum_i32(s);
-      if (lane == 0) w_head[bh] = s;
-    }
+    for (int bh = t; bh < BH; bh += 256) w_head[bh] = plan[kPlanHdr + BH + bh];
     __syncthreads();
     // rank by (work descending, index ascending)
     for (int bh = t; bh < BH; bh += 256) {
@@ -125,20 +122,26 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int *__restrict__ 
       sorted[r] = bh;
     }
     __syncthreads();
-    if (t == 0) {
-      long long load[kNumXcd];
-      int nh[kNumXcd];
-      for (int x = 0; x < kNumXcd; ++x) load[x] = 0, nh[x] = 0;
+    if (t < 64) {
+      // greedy on one wavefront: lane x < 8 holds the load of XCD x (scaled to 32 bits;
+      // +Nb per head: a row costs about one key block of fixed work); the minimum is a
+      // register-only wave reduction, so a step costs no LDS round trips
+      int shift = 0;
+      while ((((long long)BH * Nb * (Nb + 1)) >> shift) > 0x3fffffffLL) ++shift;
+      uint32_t load = t < kNumXcd ? 0u : 0xffffffffu;
+      int nh = 0;
       for (int r = 0; r < BH; ++r) {
         const int bh = sorted[r];
-        int best = 0;
-        for (int x = 1; x < kNumXcd; ++x)
-          if (load[x] < load[best]) best = x;
-        xcd_of[bh] = best;
-        rank_of[bh] = nh[best]++;
-        load[best] += w_head[bh] + Nb;  // (+Nb: a row costs about one key block of fixed work)
+        const uint32_t m = wave_min_u32(load);
+        const unsigned long long is_min = __ballot(load == m);
+        const int best = __ffsll((long long)is_min) - 1;  // least loaded XCD, lowest id on ties
+        if (t == best) {
+          xcd_of[bh] = best;
+          rank_of[bh] = nh++;
+          load += (uint32_t)(((long long)w_head[bh] + Nb) >> shift);
+        }
       }
-      for (int x = 0; x < kNumXcd; ++x) n_heads[x] = nh[x];
+      if (t < kNumXcd) n_heads[t] = nh;
     }
   } else {
     if (t < kNumXcd) n_heads[t] = BH / kNumXcd + (t < BH % kNumXcd ? 1 : 0);
@@ -148,7 +151,7 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int *__restrict__ 
     int run = 0;
     for (int x = 0; x < kNumXcd; ++x) {
       off[x] = run;
-      run += n_heads[x] * Nb;
+      run += n_heads[x];
     }
   }
   __syncthreads();
@@ -160,12 +163,12 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int *__restrict__ 
   for (int bh = t; bh < BH; bh += 256) {
     const int x = BH <= kPlanMaxHeads ? xcd_of[bh] : bh % kNumXcd;
     const int r = BH <= kPlanMaxHeads ? rank_of[bh] : bh / kNumXcd;
-    plan[kPlanHdr + bh] = off[x] + r * Nb;
+    plan[kPlanHdr + off[x] + r] = bh;
   }
 }
 
 // One workgroup per head: the Nb items of the head, longest kept list first, into the
-// head's range of seq.  Stable counting sort by count class (class 0 = the longest
+// head's range of seq, and the head's total kept count.  Stable counting sort by count class (class 0 = the longest
 // rows): thread t owns a contiguous segment of the items and one column of the class
 // histogram, so that items of a class keep their natural order.  The counts are first
 // read once, coalesced and all in flight, and kept as class bytes in LDS when they fit
@@ -178,7 +181,9 @@ __global__ __launch_bounds__(256) void attn_order_kernel(const int *__restrict__
   const int n = Nb;
   const int item0 = blockIdx.x * Nb;
   kept_count += item0;
-  int *order = plan + kPlanHdr + BH + plan[kPlanHdr + blockIdx.x];
+  int *order = plan + kPlanHdr + 2 * BH + item0;
+  __shared__ int total;
+  if (threadIdx.x == 0) total = 0;
   __shared__ int hist[kOrderClasses][256];
   __shared__ int scan[256];
   extern __shared__ unsigned char cls_lds[];  // [n] when kStaged
@@ -200,7 +205,15 @@ __global__ __launch_bounds__(256) void attn_order_kernel(const int *__restrict__
     __syncthreads();
   }
   for (int i = i0; i < i1; ++i) hist[cls_of(i)][t] += 1;
+  {
+    int w = 0;
+#pragma unroll 4
+    for (int i = t; i < n; i += 256) w += min(max(kept_count[i], 0), Nb);
+    w = wave_sum_i32(w);
+    if ((t & 63) == 0) atomicAdd(&total, w);
+  }
   __syncthreads();
+  if (t == 0) plan[kPlanHdr + BH + blockIdx.x] = total;
   // exclusive scan over the histogram flattened class-major (index = class * 256 + thread)
   int *flat = &hist[0][0];
   int sum = 0;
@@ -573,15 +586,29 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   const int x0 = (int)(blockIdx.x % kNumXcd);
   const int len0 = plan ? plan[kNumXcd + x0] : 0;
   const int off0 = plan ? plan[2 * kNumXcd + x0] : 0;
+  // (thread 0) entry i of XCD x's list: item p = i % Nb of its (i / Nb)-th head
+  const int *head_tbl = plan + kPlanHdr, *seq = plan + kPlanHdr + 2 * BH;
+  int cached_r = -1, cached_head = 0;  // the own list's head currently being walked
+  auto entry = [&](int x, int off_x, int i) -> int {
+    const int r = i / Nb, p = i - r * Nb;
+    int head;
+    if (x == x0 && r == cached_r) {
+      head = cached_head;
+    } else {
+      head = head_tbl[off_x + r];
+      if (x == x0) cached_r = r, cached_head = head;
+    }
+    return seq[head * Nb + p];
+  };
   // (thread 0) item for cursor value i_own of the own list, else from another list, else -1
   auto take = [&](int i_own) -> int {
-    if (i_own >= 0 && i_own < len0) return plan[kPlanHdr + BH + off0 + i_own];
+    if (i_own >= 0 && i_own < len0) return entry(x0, off0, i_own);
     for (int k2 = 1; k2 < kNumXcd; ++k2) {
       const int x = (x0 + k2) % kNumXcd;
       const int len = plan[kNumXcd + x];
       if (len <= 0) continue;
       const int i = atomicAdd(&plan[x], 1);
-      if (i < len) return plan[kPlanHdr + BH + plan[2 * kNumXcd + x] + i];
+      if (i < len) return entry(x, plan[2 * kNumXcd + x], i);
     }
     return -1;
   };
@@ -715,7 +742,7 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   }
   if (plan && t == 0) {
     if (i_next < 0 && len0 > 0) i_next = atomicAdd(&plan[x0], 1);  // (row without kept blocks)
-    if (i_next >= 0 && i_next < len0) item_next = plan[kPlanHdr + BH + off0 + i_next];
+    if (i_next >= 0 && i_next < len0) item_next = entry(x0, off0, i_next);
   }
 
   // ---- epilogue: normalise, stage through LDS, coalesced bf16 store -----------------------
@@ -791,8 +818,6 @@ static int launch_attn_t(const heart_shape &s, const void *q, const void *k, con
   }
   if (grid > 0x7fffffffLL) return fail(HEART_EUNSUPPORTED, "heart_block_sparse_attn: grid too large");
   if (order) {
-    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(256), 0, st, kept_count, BH, Nb, order);
-    if (int rc = check_launch("attn_plan_kernel")) return rc;
     const uint32_t mult = (uint32_t)(((kOrderClasses - 1) << 16) / Nb);
     if (Nb <= kOrderStagedMax) {
       auto okern = attn_order_kernel<true>;
@@ -812,6 +837,8 @@ static int launch_attn_t(const heart_shape &s, const void *q, const void *k, con
                          BH, Nb, mult, order);
     }
     if (int rc = check_launch("attn_order_kernel")) return rc;
+    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(256), 0, st, BH, Nb, order);
+    if (int rc = check_launch("attn_plan_kernel")) return rc;
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(BLK * 2), lds, st,
                      (const uint16_t *)q, (const uint16_t *)k, (const uint16_t *)v,

@@ -150,8 +150,8 @@ int heart_block_sparse_attn(const heart_shape *shape, const void *q, const void 
 size_t heart_attn_workspace_bytes(const heart_shape *s) {
   if (!s || s->B <= 0 || s->H <= 0 || s->N <= 0 || s->block <= 0) return 0;
   const size_t nb = ((size_t)s->N + s->block - 1) / s->block;
-  // plan header (24 ints) + one offset per head + one entry per (head, query block)
-  return ((size_t)s->B * s->H * (nb + 1) + 24) * sizeof(int);
+  // plan header (24 ints) + two entries per head + one entry per (head, query block)
+  return ((size_t)s->B * s->H * (nb + 2) + 24) * sizeof(int);
 }
 
 int heart_ubench_mfma_bf16(const void *a_bf16, const void *b_bf16, int n_workgroups, int iters,

@@ -84,9 +84,11 @@ __device__ __forceinline__ void swap_halves32(uint32_t v, uint32_t &r0, uint32_t
 // (functions, not expression macros: each argument -- a DPP read -- must be evaluated
 // exactly once and with all lanes active)
 __device__ __forceinline__ uint32_t heart_op_umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+__device__ __forceinline__ uint32_t heart_op_umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
 #define HEART_OP_ADD(a, b) ((a) + (b))
 #define HEART_OP_FMAX(a, b) fmaxf((a), (b))
 #define HEART_OP_UMAX(a, b) heart_op_umax((a), (b))
+#define HEART_OP_UMIN(a, b) heart_op_umin((a), (b))
 
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
   HEART_WAVE_REDUCE(uint32_t, v, HEART_OP_ADD);
@@ -99,6 +101,10 @@ __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
   HEART_WAVE_REDUCE(uint32_t, lo, HEART_OP_ADD);
   HEART_WAVE_REDUCE(uint32_t, hi, HEART_OP_ADD);
   return ((unsigned long long)hi << 20) + lo;
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+  HEART_WAVE_REDUCE(uint32_t, v, HEART_OP_UMIN);
+  return v;
 }
 __device__ __forceinline__ int wave_sum_i32(int v) { return (int)wave_sum_u32((uint32_t)v); }
 __device__ __forceinline__ float wave_max_f32(float v) {

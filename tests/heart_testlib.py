@@ -67,35 +67,34 @@ def check_attn_plan(ws, cnt, Nb):
     """Validate the launch plan heart_block_sparse_attn leaves in its workspace.
 
     ws: int32 workspace after the call (numpy); cnt: kept counts [B,H,Nb].  Layout: 8 cursors,
-    8 list lengths, 8 list offsets, one offset per head, then the concatenated per-XCD lists.
-    Heads go to the least loaded XCD, heaviest first (load = kept count + Nb per head); inside
-    a head the items are sorted by count class, longest first, stable."""
+    8 list lengths (items), 8 offsets into the head table, the head table (heads of XCD 0 in
+    the order it walks them, then XCD 1, ...), the total kept count per head, then per head its
+    items in launch order.  Heads go to the least loaded XCD, heaviest first (load = kept count
+    + Nb per head); inside a head the items are sorted by count class, longest first, stable."""
     BH = cnt.shape[0] * cnt.shape[1]
     n = BH * Nb
     c = np.clip(cnt.reshape(BH, Nb).astype(np.int64), 0, Nb)
     w = c.sum(1)
     order = sorted(range(BH), key=lambda h: (-w[h], h))
     load = [0] * 8
+    shift = 0
+    while (BH * Nb * (Nb + 1)) >> shift > 0x3fffffff:
+        shift += 1
     heads = [[] for _ in range(8)]
     for h in order:
         x = min(range(8), key=lambda x: (load[x], x))
         heads[x].append(h)
-        load[x] += int(w[h]) + Nb
+        load[x] += (int(w[h]) + Nb) >> shift
     lens = np.array([len(hs) * Nb for hs in heads])
-    offs = np.concatenate([[0], np.cumsum(lens)[:-1]])
+    offs = np.concatenate([[0], np.cumsum([len(hs) for hs in heads])[:-1]])
     assert np.array_equal(ws[8:16], lens), "list lengths"
-    assert np.array_equal(ws[16:24], offs), "list offsets"
+    assert np.array_equal(ws[16:24], offs), "head table offsets"
     assert (ws[0:8] >= lens).all(), "every list was drained"
-    assert ws[0:8].sum() >= n
-    head_base = np.empty(BH, np.int64)
-    for x in range(8):
-        for r, h in enumerate(heads[x]):
-            head_base[h] = offs[x] + r * Nb
-    assert np.array_equal(ws[24:24 + BH], head_base), "head offsets"
-    seq = ws[24 + BH:24 + BH + n]
-    assert np.array_equal(np.sort(seq), np.arange(n)), "the plan is a permutation of the items"
+    assert np.array_equal(ws[24:24 + BH], np.concatenate([np.array(hs, np.int64) for hs in heads])), "head table"
+    assert np.array_equal(ws[24 + BH:24 + 2 * BH], w), "head totals"
+    seq = ws[24 + 2 * BH:24 + 2 * BH + n]
     mult = (31 << 16) // Nb
     classes = 31 - ((c * mult) >> 16)
     for h in range(BH):
         want = h * Nb + np.argsort(classes[h], kind="stable")
-        assert np.array_equal(seq[head_base[h]:head_base[h] + Nb], want), f"items of head {h}"
+        assert np.array_equal(seq[h * Nb:(h + 1) * Nb], want), f"items of head {h}"

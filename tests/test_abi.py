@@ -69,7 +69,7 @@ def test_host_validation_rejects_bad_calls_without_a_gpu(lib):
     assert lib.heart_block_sparse_attn(ctypes.byref(s), None, None, None, None, None, 0.0, None,
                                        None, None, 0, None) == -2
     s.block = 128
-    assert lib.heart_attn_workspace_bytes(ctypes.byref(s)) == (1 * 2 * (1 + 1) + 24) * 4
+    assert lib.heart_attn_workspace_bytes(ctypes.byref(s)) == (1 * 2 * (1 + 2) + 24) * 4
     assert lib.heart_attn_workspace_bytes(None) == 0
     assert lib.heart_drift(1, 2, 96, None, None, None, None, None, None, 0.4, 0.8, 1, None, None,
                            None) == -2

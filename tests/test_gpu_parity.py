@@ -339,7 +339,7 @@ def test_attn_launch_plan_and_same_bits_with_and_without_it(heart):
     q, k, v = gpu(st.q), gpu(st.k), gpu(st.v)
     n = cfg.B * cfg.H * Nb
     words = heart.heart_attn_workspace_bytes(q, cfg.block) // 4
-    assert words == 24 + cfg.B * cfg.H + n
+    assert words == 24 + 2 * cfg.B * cfg.H + n
     ws = torch.full((words + 3,), -7, dtype=torch.int32, device="cuda")
     out_planned = heart.heart_block_sparse_attn(q, k, v, cfg.block, np_gpu(idx), np_gpu(cnt), workspace=ws)
     out_natural = heart.heart_block_sparse_attn(q, k, v, cfg.block, np_gpu(idx), np_gpu(cnt), workspace=None)
