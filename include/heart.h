@@ -96,8 +96,8 @@ int heart_drift(int B, int H, int D, const float *qmean, const float *kmean, flo
  * Block importance and top-p block mask for refreshed heads (top-p rule of
  * Sec. 3.2; minimal set reaching the mass, Eq. 1; scale 1/sqrt(D) of the
  * query-key interaction in the appendix; p = 1 is the dense value).
- *   scores P[i,j] = softmax_j( qblk_i . kblk_j / sqrt(D) )       (dot products fp64,
- *                   exponentials fp32)
+ *   scores P[i,j] = softmax_j( qblk_i . kblk_j / sqrt(D) )       (dot products on the
+ *                   fp64 matrix cores, exponentials fp32)
  *   per row i: rank key blocks by P descending, equal scores by lower index; with
  *   u_j = floor(P_j * 2^30) and T = floor(tau_h * 2^24) keep the shortest prefix
  *   whose  sum(u) * 2^24 >= T * (row total of u);  at least max(1, min_keep)
@@ -115,7 +115,7 @@ int heart_drift(int B, int H, int D, const float *qmean, const float *kmean, flo
  *            row in its first kept_count entries (the rest is left untouched);
  *          kept_count int32 [B,H,Nb];
  *          scores_out fp32 [B,H,Nb,Nb] or NULL.
- * Supported: Nb <= HEART_MAX_NB; D a multiple of 4, D <= 128.
+ * Supported: Nb <= HEART_MAX_NB; D a multiple of 16, D <= 128.
  */
 int heart_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float *kblk,
                     const float *scores_in, const float *tau, const unsigned char *refresh,

@@ -99,9 +99,9 @@ int heart_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float 
   if (!scores_in) {
     if (!qblk || !kblk)
       return fail(HEART_EINVAL, "heart_mask_topp: need qblk and kblk, or scores_in");
-    if (D <= 0 || D % 4 != 0 || D > 128)
+    if (D <= 0 || D % 16 != 0 || D > 128)
       return fail(HEART_EUNSUPPORTED,
-                  "heart_mask_topp: D must be a positive multiple of 4, <= 128 (got %d)", D);
+                  "heart_mask_topp: D must be a positive multiple of 16, <= 128 (got %d)", D);
     if (!aligned16(qblk) || !aligned16(kblk))
       return fail(HEART_EUNSUPPORTED, "heart_mask_topp: qblk/kblk must be 16-byte aligned");
   }

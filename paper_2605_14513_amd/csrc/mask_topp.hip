@@ -3,13 +3,16 @@
 // them until the accumulated importance reaches tau; Eq. 1: the minimal such set;
 // 1/sqrt(D) interaction scale from the appendix on query-key stability).
 //
-// One workgroup (4 wavefronts) owns R = 8 query-block rows of one head.
-//   Phase A  logits[r][j] = qblk_r . kblk_j / sqrt(D): the key blocks stream through
-//            LDS in chunks of 32 columns (coalesced loads, next chunk in flight),
-//            one (row, column) dot product per lane and chunk in fp64 fused
-//            multiply-add (on this chip fp64 FMA issues at the rate of unpacked
-//            fp32 FMA, and it takes the dot product out of the error budget of the
-//            scores).  The R query rows sit in LDS as fp64.
+// One workgroup (8 wavefronts) owns R = 16 query-block rows of one head.
+//   Phase A  logits[r][j] = qblk_r . kblk_j / sqrt(D) on the fp64 matrix cores
+//            (v_mfma_f64_16x16x4_f64: a 16 x 16 tile of logits per wavefront, the
+//            contraction over d in steps of 4; fp64 takes the dot product out of the
+//            error budget of the scores).  The contraction order over d is free, so
+//            lane group g = lane / 16 takes the d range [g D/4, (g+1) D/4): a lane then
+//            reads D/4 consecutive floats of one block mean (16-byte loads straight from
+//            global memory, no LDS staging) and converts them to fp64 on the way in.
+//            The 16 query rows sit in LDS as fp64; the key blocks of the next tile are
+//            in flight while the current tile is multiplied.
 //   Phase B  row softmax, one wavefront per row, fp32 with the accurate expf.
 //   Phase C  top-p selection, one wavefront per row, without sorting: the kept set
 //            is "every score above a threshold value v*, plus the lowest-index
@@ -24,12 +27,13 @@
 
 namespace heart {
 
-constexpr int kRows = 8;       // query-block rows per workgroup
-constexpr int kCols = 32;      // key-block columns staged through LDS at a time (kRows * kCols = 256 lanes)
-constexpr int kMaxStage = 4;   // float4 per lane for one staged chunk at D = 128
+constexpr int kRows = 16;      // query-block rows per workgroup (one MFMA tile high)
+constexpr int kMaxF4 = 8;      // float4 per lane and tile at D = 128 (D/16)
+constexpr int kWaves = 8;      // wavefronts per workgroup: two rows each in the selection
+typedef __attribute__((ext_vector_type(4))) double f64x4_t;
 
 template <int CMAX>  // slots per lane; handles Nb <= 64 * CMAX
-__global__ __launch_bounds__(256) void mask_topp_kernel(
+__global__ __launch_bounds__(64 * kWaves) void mask_topp_kernel(
     int H, int Nb, int D, const float *__restrict__ qblk, const float *__restrict__ kblk,
     const float *__restrict__ scores_in, const float *__restrict__ tau,
     const unsigned char *__restrict__ refresh, int n_always_kv, int n_dense_q, int min_keep,
@@ -37,9 +41,8 @@ __global__ __launch_bounds__(256) void mask_topp_kernel(
     float *__restrict__ scores_out) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   constexpr int NBP = 64 * CMAX;
-  double *sQ = reinterpret_cast<double *>(smem_raw);                       // [kRows][D]
-  float *sP = reinterpret_cast<float *>(smem_raw + (size_t)kRows * D * 8);  // [kRows][NBP]
-  float *sKt = sP + kRows * NBP;                                            // [kCols][D + 4]
+  float *sP = reinterpret_cast<float *>(smem_raw);  // [kRows][NBP] logits of the rows
+  double *sQ = reinterpret_cast<double *>(smem_raw + (size_t)kRows * NBP * 4);  // [kRows][D + 2]
 
   const int groups = (Nb + kRows - 1) / kRows;
   const long long bh = blockIdx.x / groups;
@@ -51,59 +54,59 @@ __global__ __launch_bounds__(256) void mask_topp_kernel(
 
   if (!scores_in) {
     // ---- Phase A: logits -------------------------------------------------------
-    for (int e = threadIdx.x; e < kRows * D; e += 256) {
-      int r = e / D, d = e % D;
-      int i = i0 + r;
-      sQ[e] = i < Nb ? (double)qblk[((size_t)bh * Nb + i) * D + d] : 0.0;
-    }
-    // K blocks travel through LDS in chunks of kCols columns with coalesced 16-byte
-    // loads (the next chunk is in flight in registers while this one is consumed);
-    // thread (r, c) = (t / kCols, t % kCols) then owns one (query row, key column) dot
-    // product per chunk.  Row stride D + 4 floats spreads the columns over the banks.
-    const int D4 = D / 4;                      // float4 per K row
-    const int per_thread = (kCols * D4 + 255) / 256;
-    const int SKT = D + 4;
+    // MFMA operand layout (16x16x4 fp64): A lane L = (row L%16, k L/16), B lane L =
+    // (k L/16, column L%16), D lane L register r = (row L/16 + 4 r, column L%16).
+    const int n16 = lane & 15, g = lane >> 4;
+    const int nf4 = D / 16;  // float4 per lane: its D/4 consecutive d values
+    const float4 *qg = reinterpret_cast<const float4 *>(qblk + (size_t)bh * Nb * D);
     const float4 *kg = reinterpret_cast<const float4 *>(kblk + (size_t)bh * Nb * D);
-    float4 stage[kMaxStage];
-    auto load_chunk = [&](int c0) {
+    // the 16 query rows as fp64 in LDS (row stride D + 2 doubles: the 16 rows a quarter of
+    // the lanes reads fall into distinct banks); keeping them there rather than in 64
+    // registers lets more wavefronts share a SIMD, which the latency-bound selection needs
+    const int SQ = D + 2;
+    for (int e = threadIdx.x; e < kRows * (D / 4); e += 64 * kWaves) {
+      const int r = e / (D / 4), d4 = e % (D / 4);
+      float4 t4 = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (i0 + r < Nb) t4 = qg[(size_t)(i0 + r) * (D / 4) + d4];
+      double *dst = sQ + r * SQ + d4 * 4;
+      dst[0] = (double)t4.x;
+      dst[1] = (double)t4.y;
+      dst[2] = (double)t4.z;
+      dst[3] = (double)t4.w;
+    }
+    __syncthreads();
+    const double *qrow = sQ + n16 * SQ + g * (D / 4);  // this lane's A operands, step by step
+    auto load_tile = [&](float4 (&dst)[kMaxF4], int tile) {
+      const int j = tile * 16 + n16;
 #pragma unroll
-      for (int u = 0; u < kMaxStage; ++u) {
-        const int e = threadIdx.x + u * 256;
-        const int col = e / D4, d4 = e % D4;
-        stage[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (u < per_thread && col < kCols && c0 + col < Nb) stage[u] = kg[(size_t)(c0 + col) * D4 + d4];
-      }
-    };
-    auto store_chunk = [&]() {
-#pragma unroll
-      for (int u = 0; u < kMaxStage; ++u) {
-        const int e = threadIdx.x + u * 256;
-        const int col = e / D4, d4 = e % D4;
-        if (u < per_thread && col < kCols) *reinterpret_cast<float4 *>(sKt + col * SKT + d4 * 4) = stage[u];
+      for (int u = 0; u < kMaxF4; ++u) {
+        dst[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (u < nf4 && j < Nb) dst[u] = kg[(size_t)j * (D / 4) + g * nf4 + u];
       }
     };
     const double inv_sqrt_d = 1.0 / sqrt((double)D);
-    const int c = threadIdx.x % kCols, r = threadIdx.x / kCols;
-    load_chunk(0);
-    for (int c0 = 0; c0 < Nb; c0 += kCols) {
-      __syncthreads();  // previous chunk consumed (first pass: sQ written)
-      store_chunk();
-      __syncthreads();
-      if (c0 + kCols < Nb) load_chunk(c0 + kCols);
-      // four independent fp64 chains (a single one would be bound by FMA latency)
-      double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
-      const float *kr = sKt + c * SKT;
-      const double *qr = sQ + r * D;
-#pragma unroll 4
-      for (int d4 = 0; d4 < D4; ++d4) {
-        const float4 kv = *reinterpret_cast<const float4 *>(kr + d4 * 4);
-        a0 = fma((double)kv.x, qr[d4 * 4 + 0], a0);
-        a1 = fma((double)kv.y, qr[d4 * 4 + 1], a1);
-        a2 = fma((double)kv.z, qr[d4 * 4 + 2], a2);
-        a3 = fma((double)kv.w, qr[d4 * 4 + 3], a3);
+    const int ntiles = (Nb + 15) / 16;
+    float4 kc[kMaxF4], kn[kMaxF4];
+    if (wave < ntiles) load_tile(kc, wave);
+    for (int tile = wave; tile < ntiles; tile += kWaves) {
+      if (tile + kWaves < ntiles) load_tile(kn, tile + kWaves);
+      f64x4_t acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int u = 0; u < kMaxF4; ++u) {
+        if (u < nf4) {  // uniform
+          acc = __builtin_amdgcn_mfma_f64_16x16x4f64(qrow[4 * u + 0], (double)kc[u].x, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f64_16x16x4f64(qrow[4 * u + 1], (double)kc[u].y, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f64_16x16x4f64(qrow[4 * u + 2], (double)kc[u].z, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f64_16x16x4f64(qrow[4 * u + 3], (double)kc[u].w, acc, 0, 0, 0);
+        }
       }
-      const double acc = (a0 + a1) + (a2 + a3);
-      if (c0 + c < Nb) sP[r * NBP + c0 + c] = (float)(acc * inv_sqrt_d);
+      const int j = tile * 16 + n16;
+      if (j < Nb) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sP[(g + 4 * r) * NBP + j] = (float)(acc[r] * inv_sqrt_d);
+      }
+#pragma unroll
+      for (int u = 0; u < kMaxF4; ++u) kc[u] = kn[u];
     }
     __syncthreads();
   }
@@ -111,7 +114,7 @@ __global__ __launch_bounds__(256) void mask_topp_kernel(
   const float tau_h = tau[h];
   const unsigned long long lt_mask = (1ull << lane) - 1ull;
 
-  for (int r = wave; r < kRows; r += 4) {
+  for (int r = wave; r < kRows; r += kWaves) {
     const int i = i0 + r;
     if (i >= Nb) break;  // wave-uniform
     const size_t row = (size_t)bh * Nb + i;
@@ -269,11 +272,19 @@ static int launch_cmax(int B, int H, int Nb, int D, const float *qblk, const flo
                        int n_always_kv, int n_dense_q, int min_keep, unsigned char *mask,
                        int *kept_idx, int *kept_count, float *scores_out, hipStream_t st) {
   int groups = (Nb + kRows - 1) / kRows;
-  size_t lds = scores_in ? 0
-                         : (size_t)kRows * D * 8 + (size_t)kRows * 64 * CMAX * 4 +
-                               (size_t)kCols * (D + 4) * 4;
+  size_t lds = scores_in ? 0 : (size_t)kRows * 64 * CMAX * 4 + (size_t)kRows * (D + 2) * 8;
   long long nwg = (long long)B * H * groups;
-  hipLaunchKernelGGL(mask_topp_kernel<CMAX>, dim3((unsigned)nwg), dim3(256), lds, st, H, Nb, D,
+  if (lds > 64 * 1024) {
+    static bool attr_set = false;  // per instantiation: the attribute is per function
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(mask_topp_kernel<CMAX>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+      if (e != hipSuccess)
+        return fail(HEART_EHIP, "hipFuncSetAttribute(mask kernel LDS): %s", hipGetErrorString(e));
+      attr_set = true;
+    }
+  }
+  hipLaunchKernelGGL(mask_topp_kernel<CMAX>, dim3((unsigned)nwg), dim3(64 * kWaves), lds, st, H, Nb, D,
                      qblk, kblk, scores_in, tau, refresh, n_always_kv, n_dense_q, min_keep, mask,
                      kept_idx, kept_count, scores_out);
   return check_launch("mask_topp_kernel");
