@@ -127,6 +127,10 @@ CONFIGS: Dict[str, HeartConfig] = {
         name="small_d64", B=1, H=3, D=64, grid=(3, 11, 13), block=64, seed=13,
         steps=2, tau_spec=("uniform", 0.8, 0.98), delta=1.0, schedule="jumps",
     ),
+    "small_d64_b128": HeartConfig(
+        name="small_d64_b128", B=2, H=2, D=64, grid=(4, 9, 17), block=128, seed=14,
+        steps=2, tau_spec=("uniform", 0.8, 0.98), delta=1.0, schedule="jumps",
+    ),
 }
 
 

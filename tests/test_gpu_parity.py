@@ -23,7 +23,7 @@ from heart_testlib import (check_attn_plan, ATTN_ATOL, assert_lists_equal, asser
 
 pytestmark = pytest.mark.gpu
 
-SMALL = ["tiny", "small_ragged", "small_text", "small_d64"]
+SMALL = ["tiny", "small_ragged", "small_text", "small_d64", "small_d64_b128"]
 
 
 @pytest.fixture(scope="module")
