@@ -39,6 +39,12 @@ def parse_args():
     ap.add_argument("--workload", default="wan14b_480p")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gate", default="0.4,0.8", help="layer gate lo,hi (0,1 disables)")
+    ap.add_argument("--policy-sweep", action="store_true",
+                    help="instead of the headline step: run a multi-layer, multi-step TMR schedule "
+                         "(dense warm-up, then sparse steps) under each reuse policy and print one "
+                         "JSON line with refresh counts and kernel times per policy")
+    ap.add_argument("--sweep-steps", type=int, default=15)
+    ap.add_argument("--sweep-layers", type=int, default=2)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -111,6 +117,41 @@ def measured_ceilings(heart, torch, q0, k0):
     out["hbm_copy_gbs"] = best
     del src, dst
     return out
+
+
+def policy_sweep(args, heart, torch, g, steps_in, tau, delta):
+    """Structure of the paper's reuse-policy ablation on synthetic inputs: refresh counts and
+    time per policy over L layers x 2 guidance branches x S denoising steps (the first 5 dense).
+    Quality metrics are out of reach here (they need the models); this reports cost only."""
+    from paper_2605_14513_amd.tmr import TmrConfig, TmrDriver
+
+    cfg = g.cfg
+    S = len(steps_in)
+    res = []
+    for policy in ("always", "heart", "interval:4", "warmup:5"):
+        drv = TmrDriver(TmrConfig(B=cfg.B, H=cfg.H, N=cfg.N, D=cfg.D, block=cfg.block, tau=tau,
+                                  delta=delta, policy=policy, dense_steps=5,
+                                  n_always_kv_blocks=cfg.n_text_blocks,
+                                  n_dense_q_blocks=cfg.n_text_blocks),
+                        n_layers=args.sweep_layers, n_branches=2, record=True, time_kernels=True)
+        out = torch.empty_like(steps_in[0][0])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(args.sweep_steps):
+            for layer in range(args.sweep_layers):
+                for br in range(2):
+                    q, k, v = steps_in[(s + layer + 3 * br) % S]
+                    drv.attention(layer, br, s, q, k, v, out=out)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        summ = drv.summary()
+        summ["wall_ms_per_call"] = wall * 1e3 / summ["calls"]
+        res.append(summ)
+        print(f"[bench] policy {policy}: {summ}", file=sys.stderr, flush=True)
+        del drv
+    return {"metric": "TMR policy sweep (cost only), " + cfg.name, "layers": args.sweep_layers,
+            "branches": 2, "steps": args.sweep_steps, "dense_steps": 5, "policies": res,
+            "data": "synthetic"}
 
 
 def cpu_baseline(name, tau_all, delta_all):
@@ -203,6 +244,10 @@ def main():
     del st
     print(f"[bench] inputs resident after {time.perf_counter() - t_setup:.1f} s", file=sys.stderr,
           flush=True)
+
+    if args.policy_sweep:
+        print(json.dumps(policy_sweep(args, heart, torch, g, steps_in, tau, delta)))
+        return
 
     f32 = dict(dtype=torch.float32, device=dev)
     qblk = torch.empty((B, H, Nb, D), **f32); kblk = torch.empty((B, H, Nb, D), **f32)
