@@ -296,6 +296,36 @@ def main():
                     for i in range(K)])  # ms
     pool_ms, drift_ms, mask_ms, attn_ms = per.mean(0)
 
+    # ---- launch overhead: schedule step 1 repeated K times, eagerly and as one HIP graph ----
+    # (extra information; `value` comes from the eager region above.  After the first
+    # repetition nothing drifts any more, so these steps are pool + drift + attention.)
+    launch = None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            one_step(1)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        t0e = time.perf_counter()
+        for _ in range(K):
+            one_step(1)
+        torch.cuda.synchronize()
+        eager_rep_ms = (time.perf_counter() - t0e) * 1e3 / K
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            one_step(1)
+        torch.cuda.synchronize()
+        t0g = time.perf_counter()
+        for _ in range(K):
+            gr.replay()
+        torch.cuda.synchronize()
+        launch = {"repeated_step_eager_ms": eager_rep_ms,
+                  "repeated_step_hip_graph_ms": (time.perf_counter() - t0g) * 1e3 / K}
+        del gr
+    except Exception as e:  # optional figure
+        print(f"[bench] HIP graph timing skipped: {e}", file=sys.stderr, flush=True)
+
     # ---- untimed replay of the same K steps to count kept-block FLOPs and refresh ratio ----
     has.zero_(); kcnt.zero_()
     flops, dens, refr = [], [], []
@@ -337,6 +367,7 @@ def main():
                                 "step / wall time of the whole step (pool+drift+mask+attention)",
         },
         "mask_refresh_us_per_step": (pool_ms + drift_ms + mask_ms) * 1e3,
+        "launch_overhead": launch,
         "kernels_us": {"pool_qk": pool_ms * 1e3, "drift": drift_ms * 1e3,
                        "mask_topp": mask_ms * 1e3, "block_sparse_attn": attn_ms * 1e3},
         "attn_kept_tflops": attn_tflops,
