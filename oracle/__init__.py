@@ -15,3 +15,4 @@ from .heart_oracle import (  # noqa: F401
     dense_attn,
     num_threads,
 )
+from . import ebc_oracle  # noqa: F401
