@@ -43,6 +43,10 @@ def parse_args():
                     help="instead of the headline step: run a multi-layer, multi-step TMR schedule "
                          "(dense warm-up, then sparse steps) under each reuse policy and print one "
                          "JSON line with refresh counts and kernel times per policy")
+    ap.add_argument("--ebc-demo", action="store_true",
+                    help="instead of the headline step: calibrate per-head thresholds on the workload "
+                         "(errors measured with the library's sparse attention on synthetic tensors) "
+                         "and print one JSON line comparing them with the shared threshold 0.9")
     ap.add_argument("--sweep-steps", type=int, default=15)
     ap.add_argument("--sweep-layers", type=int, default=2)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -154,6 +158,71 @@ def policy_sweep(args, heart, torch, g, steps_in, tau, delta):
             "data": "synthetic"}
 
 
+def ebc_demo(args, heart, torch, g, steps_in):
+    """Error-guided Budgeted Calibration on synthetic tensors: the attention output of a head
+    stands in for the denoising velocity (the models are not available), the candidates are
+    shared thresholds, the budget is the sparsity of the shared threshold 0.9."""
+    import numpy as np
+
+    cfg = g.cfg
+    B, H, N, D, Nb, blk, nt = cfg.B, cfg.H, cfg.N, cfg.D, cfg.Nb, cfg.block, cfg.n_text_blocks
+    T, Yg, Xg = cfg.grid
+    q, k, v = steps_in[0]
+    qblk, kblk, _, _ = heart.heart_pool_qk(q, k, blk)
+    cands = [0.6, 0.7, 0.8, 0.85, 0.9, 0.95, 0.98, 1.0]
+    ones = torch.ones(H, device=q.device)
+    _, didx, dcnt = heart.heart_mask_topp(qblk, kblk, ones, n_always_kv_blocks=nt, n_dense_q_blocks=nt)
+    dense = heart.heart_block_sparse_attn(q, k, v, blk, didx, dcnt)
+    n_grid = T * Yg * Xg
+
+    def as_field(x, h):  # [B, N, D] of head h -> [B*D, T, Y, X] over the video tokens
+        return x[:, h, N - n_grid:].float().permute(0, 2, 1).reshape(B * D, T, Yg, Xg).contiguous()
+
+    E = np.zeros((H, len(cands))); S = np.zeros((H, len(cands)))
+    ws = torch.empty(heart.heart_ebc_workspace_bytes(B * D, T, Yg, Xg), dtype=torch.uint8, device=q.device)
+    dens = [as_field(dense, h) for h in range(H)]
+    ev = []
+    for ci, tc in enumerate(cands):
+        tau = torch.full((H,), tc, device=q.device)
+        _, idx, cnt = heart.heart_mask_topp(qblk, kblk, tau, n_always_kv_blocks=nt, n_dense_q_blocks=nt)
+        out = heart.heart_block_sparse_attn(q, k, v, blk, idx, cnt)
+        cnt_h = cnt.float().sum(dim=(0, 2)).cpu().numpy()
+        for h in range(H):
+            err = as_field(out, h) - dens[h]
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            r = heart.heart_ebc_band_error(err, dens[h], workspace=ws)
+            e1.record()
+            ev.append((e0, e1))
+            E[h, ci] = r[0].item()
+            S[h, ci] = 1.0 - cnt_h[h] / (B * Nb * Nb)
+    torch.cuda.synchronize()
+    shared = cands.index(0.9)
+    budget = float(S[:, shared].mean())
+    t0 = time.perf_counter()
+    choice, total = heart.heart_ebc_select(E, S, budget)
+    t_sel = time.perf_counter() - t0
+    # the same solver at the size of a full model: 40 layers x 40 heads, tables tiled with noise
+    rng = np.random.default_rng(0)
+    reps = max(1, 1600 // H)
+    Eb = np.tile(E, (reps, 1)) * rng.uniform(0.5, 2.0, size=(reps * H, 1))
+    Sb = np.tile(S, (reps, 1))
+    t0 = time.perf_counter()
+    _, total_big = heart.heart_ebc_select(Eb, Sb, budget)
+    t_big = time.perf_counter() - t0
+    return {
+        "metric": "EBC on synthetic tensors, " + cfg.name, "data": "synthetic",
+        "candidates": cands, "budget_mean_sparsity": budget,
+        "shared_threshold_error": float(E[:, shared].sum()), "calibrated_error": total,
+        "calibrated_thresholds": [cands[c] for c in choice],
+        "calibrated_mean_sparsity": float(S[np.arange(H), choice].mean()),
+        "band_error_us_per_call": float(np.median([a.elapsed_time(b) for a, b in ev]) * 1e3),
+        "band_error_tensor": [B * D, T, Yg, Xg],
+        "select_ms": t_sel * 1e3, "select_ms_at_1600_heads": t_big * 1e3,
+        "shared_vs_calibrated_error_at_1600_heads": [float(Eb[:, shared].sum()), total_big],
+    }
+
+
 def cpu_baseline(name, tau_all, delta_all):
     """Oracle timed on host cores on a bounded sample of the same workload."""
     import numpy as np
@@ -247,6 +316,9 @@ def main():
 
     if args.policy_sweep:
         print(json.dumps(policy_sweep(args, heart, torch, g, steps_in, tau, delta)))
+        return
+    if args.ebc_demo:
+        print(json.dumps(ebc_demo(args, heart, torch, g, steps_in)))
         return
 
     f32 = dict(dtype=torch.float32, device=dev)

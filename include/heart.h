@@ -153,6 +153,31 @@ int heart_block_sparse_attn(const heart_shape *shape, const void *q_bf16, const 
 size_t heart_attn_workspace_bytes(const heart_shape *shape);
 
 /*
+ * Error-guided Budgeted Calibration (Sec. 4.3): offline, not on the serving path.
+ *
+ * heart_ebc_band_error: the frequency-weighted velocity error of Eq. 6 (bands and weights:
+ *   appendix on the frequency-aware velocity error).  err, dense: DEVICE fp32 [C,T,Y,X]
+ *   contiguous (sparse-induced error and dense reference; energies are summed over the C
+ *   leading entries, the transform axes are T, Y, X, each <= 1024); weights4_host: HOST
+ *   array of the four band weights (LL, LH, HL, HH); epsilon >= 0.  out6: DEVICE double[6]
+ *   = {weighted error, E_LL, E_LH, E_HL, E_HH, spectral energy of dense}, in the units of an
+ *   unnormalised DFT.  workspace: DEVICE, heart_ebc_workspace_bytes(C,T,Y,X), 16-byte
+ *   aligned.  Computed without a transform (band projections are circular convolutions
+ *   with Dirichlet kernels, in fp64); results are reproducible run to run.
+ * heart_ebc_select: the one-candidate-per-head selection of Eq. 5, solved exactly on the
+ *   HOST.  error_host, sparsity_host: [n_heads, n_candidates] doubles; minimises the summed
+ *   error subject to mean sparsity >= min_mean_sparsity; choice_host: int[n_heads];
+ *   total_error_host: double[1].  HEART_EINVAL if the budget cannot be met.
+ */
+int heart_ebc_band_error(long long C, int T, int Y, int X, const float *err, const float *dense,
+                         const double *weights4_host, double epsilon, void *workspace,
+                         size_t workspace_bytes, double *out6, void *stream);
+size_t heart_ebc_workspace_bytes(long long C, int T, int Y, int X);
+int heart_ebc_select(int n_heads, int n_candidates, const double *error_host,
+                     const double *sparsity_host, double min_mean_sparsity, int *choice_host,
+                     double *total_error_host);
+
+/*
  * Diagnostics for roofline accounting (not part of the method).
  * heart_ubench_mfma_bf16: n_workgroups workgroups of 4 wavefronts each issue 16 * iters
  *   v_mfma_f32_32x32x16_bf16 on register operands taken from a_bf16 / b_bf16 (device,

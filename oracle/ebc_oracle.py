@@ -70,3 +70,26 @@ def select_bruteforce(E: np.ndarray, S: np.ndarray, s_min: float):
         if e < best_e:
             best, best_e = choice, e
     return (None, np.inf) if best is None else (np.array(best), float(best_e))
+
+
+def select_dp_integer(E: np.ndarray, S_int: np.ndarray, need_total: int) -> float:
+    """Eq. 5 for INTEGER sparsity scores by dynamic programming over the total (exact, for
+    mid-size checks): minimum summed error with sum of S_int >= need_total; inf if infeasible."""
+    E = np.asarray(E, dtype=np.float64)
+    S_int = np.asarray(S_int, dtype=np.int64)
+    n, k = E.shape
+    cap = int(need_total)
+    best = np.full(cap + 1, np.inf)  # best[t] = least error with total sparsity min(total, cap) == t
+    best[0] = 0.0
+    for i in range(n):
+        new = np.full(cap + 1, np.inf)
+        for c in range(k):
+            for t in range(cap + 1):
+                if best[t] == np.inf:
+                    continue
+                t2 = min(cap, t + int(S_int[i, c]))
+                v = best[t] + E[i, c]
+                if v < new[t2]:
+                    new[t2] = v
+        best = new
+    return float(best[cap])

@@ -8,6 +8,9 @@ from .binding import (  # noqa: F401
     heart_attn_workspace_bytes,
     heart_block_sparse_attn,
     heart_drift,
+    heart_ebc_band_error,
+    heart_ebc_select,
+    heart_ebc_workspace_bytes,
     heart_last_error,
     heart_mask_topp,
     heart_pool_qk,

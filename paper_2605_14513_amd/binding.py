@@ -68,6 +68,13 @@ def load_library() -> ctypes.CDLL:
     lib.heart_ubench_mfma_bf16.restype = ci
     lib.heart_ubench_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.heart_ubench_copy.restype = ci
+    lib.heart_ebc_band_error.argtypes = [ctypes.c_longlong, ci, ci, ci, vp, vp, vp, ctypes.c_double, vp,
+                                         ctypes.c_size_t, vp, vp]
+    lib.heart_ebc_band_error.restype = ci
+    lib.heart_ebc_workspace_bytes.argtypes = [ctypes.c_longlong, ci, ci, ci]
+    lib.heart_ebc_workspace_bytes.restype = ctypes.c_size_t
+    lib.heart_ebc_select.argtypes = [ci, ci, vp, vp, ctypes.c_double, vp, vp]
+    lib.heart_ebc_select.restype = ci
     lib.heart_last_error.restype = ctypes.c_char_p
     _lib = lib
     return lib
@@ -277,3 +284,50 @@ def heart_ubench_copy(src, dst):
     rc = lib.heart_ubench_copy(_dev(src, src.dtype, "src"), _dev(dst, dst.dtype, "dst"), nbytes, _stream())
     _check("heart_ubench_copy", rc)
     return 2.0 * nbytes
+
+
+def heart_ebc_workspace_bytes(C: int, T: int, Y: int, X: int) -> int:
+    return int(load_library().heart_ebc_workspace_bytes(C, T, Y, X))
+
+
+def heart_ebc_band_error(err, dense, weights=(1.0, 0.5, 0.01, 0.01), epsilon: float = 1e-10,
+                         workspace=None, out=None):
+    """Frequency-weighted velocity error of fp32 GPU tensors [..., T, Y, X] (leading axes are
+    summed over).  Returns a GPU float64 tensor [6]: error, E_LL, E_LH, E_HL, E_HH, dense energy."""
+    lib = load_library()
+    if err.shape != dense.shape or err.dim() < 3:
+        raise ValueError("err and dense must have the same shape [..., T, Y, X]")
+    T, Y, X = (int(v) for v in err.shape[-3:])
+    C = int(err.numel() // (T * Y * X))
+    need = int(lib.heart_ebc_workspace_bytes(C, T, Y, X))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=err.device)
+    if out is None:
+        out = torch.empty(6, dtype=torch.float64, device=err.device)
+    w = (ctypes.c_double * 4)(*[float(x) for x in weights])
+    rc = lib.heart_ebc_band_error(C, T, Y, X, _dev(err, torch.float32, "err"),
+                                  _dev(dense, torch.float32, "dense"), w, float(epsilon),
+                                  _dev(workspace, workspace.dtype, "workspace"),
+                                  workspace.numel() * workspace.element_size(),
+                                  _dev(out, torch.float64, "out"), _stream())
+    _check("heart_ebc_band_error", rc)
+    return out
+
+
+def heart_ebc_select(error, sparsity, min_mean_sparsity: float):
+    """Exact one-candidate-per-head selection (host).  error, sparsity: array-likes
+    [n_heads, n_candidates].  Returns (choice int32 numpy [n_heads], total error)."""
+    import numpy as np
+
+    lib = load_library()
+    E = np.ascontiguousarray(error, dtype=np.float64)
+    S = np.ascontiguousarray(sparsity, dtype=np.float64)
+    if E.ndim != 2 or E.shape != S.shape:
+        raise ValueError("error and sparsity must be [n_heads, n_candidates]")
+    choice = np.zeros(E.shape[0], dtype=np.int32)
+    total = ctypes.c_double(0.0)
+    rc = lib.heart_ebc_select(E.shape[0], E.shape[1], E.ctypes.data_as(ctypes.c_void_p),
+                              S.ctypes.data_as(ctypes.c_void_p), float(min_mean_sparsity),
+                              choice.ctypes.data_as(ctypes.c_void_p), ctypes.byref(total))
+    _check("heart_ebc_select", rc)
+    return choice, float(total.value)

@@ -2,6 +2,7 @@
 // Everything is checked on the host before a kernel is enqueued, so that a bad
 // call returns an error code instead of a memory fault on the device.
 #include <stdarg.h>
+#include <cmath>
 #include <stdio.h>
 
 #include "heart_internal.h"
@@ -152,6 +153,52 @@ size_t heart_attn_workspace_bytes(const heart_shape *s) {
   const size_t nb = ((size_t)s->N + s->block - 1) / s->block;
   // plan header (24 ints) + two entries per head + one entry per (head, query block)
   return ((size_t)s->B * s->H * (nb + 2) + 24) * sizeof(int);
+}
+
+int heart_ebc_band_error(long long C, int T, int Y, int X, const float *err, const float *dense,
+                         const double *weights4_host, double epsilon, void *workspace,
+                         size_t workspace_bytes, double *out6, void *stream) {
+  clear_error();
+  if (C <= 0 || T <= 0 || Y <= 0 || X <= 0)
+    return fail(HEART_EINVAL, "heart_ebc_band_error: sizes must be positive");
+  if (T > 1024 || Y > 1024 || X > 1024)
+    return fail(HEART_EUNSUPPORTED, "heart_ebc_band_error: axes longer than 1024 are not supported");
+  if (!err || !dense || !weights4_host || !workspace || !out6)
+    return fail(HEART_EINVAL, "heart_ebc_band_error: NULL pointer argument");
+  if (!(epsilon >= 0.0)) return fail(HEART_EINVAL, "heart_ebc_band_error: epsilon must be >= 0");
+  if (!aligned16(workspace) || workspace_bytes < heart_ebc_workspace_bytes(C, T, Y, X))
+    return fail(HEART_EINVAL, "heart_ebc_band_error: workspace of %zu bytes, need %zu (16-byte aligned)",
+                workspace_bytes, heart_ebc_workspace_bytes(C, T, Y, X));
+  return launch_ebc_band_error(C, T, Y, X, err, dense, weights4_host, epsilon, (double *)workspace,
+                               out6, (hipStream_t)stream);
+}
+
+size_t heart_ebc_workspace_bytes(long long C, int T, int Y, int X) {
+  if (C <= 0 || T <= 0 || Y <= 0 || X <= 0) return 0;
+  return ebc_workspace_bytes(C, T, Y, X);
+}
+
+int heart_ebc_select(int n_heads, int n_candidates, const double *error_host,
+                     const double *sparsity_host, double min_mean_sparsity, int *choice_host,
+                     double *total_error_host) {
+  clear_error();
+  if (n_heads <= 0 || n_candidates <= 0)
+    return fail(HEART_EINVAL, "heart_ebc_select: n_heads and n_candidates must be positive");
+  if (!error_host || !sparsity_host || !choice_host || !total_error_host)
+    return fail(HEART_EINVAL, "heart_ebc_select: NULL pointer argument");
+  for (size_t i = 0; i < (size_t)n_heads * n_candidates; ++i)
+    if (!std::isfinite(error_host[i]) || !std::isfinite(sparsity_host[i]))
+      return fail(HEART_EINVAL, "heart_ebc_select: table entry %zu is not finite", i);
+  const int rc = ebc_select_host(n_heads, n_candidates, error_host, sparsity_host,
+                                 min_mean_sparsity, choice_host, total_error_host, nullptr);
+  if (rc == 1)
+    return fail(HEART_EINVAL, "heart_ebc_select: the sparsity budget %g cannot be met",
+                min_mean_sparsity);
+  if (rc == 2)
+    return fail(HEART_EUNSUPPORTED,
+                "heart_ebc_select: optimality not proved within the search limit (the best "
+                "selection found is in choice_host)");
+  return HEART_OK;
 }
 
 int heart_ubench_mfma_bf16(const void *a_bf16, const void *b_bf16, int n_workgroups, int iters,

@@ -131,6 +131,12 @@ int launch_attn(const heart_shape &s, const void *q, const void *k, const void *
                 const int *kept_idx, const int *kept_count, float scale, void *out, float *lse,
                 int *order, hipStream_t st);
 
+int launch_ebc_band_error(long long C, int T, int Y, int X, const float *err, const float *dense,
+                          const double *w, double epsilon, double *ws, double *out,
+                          hipStream_t st);
+size_t ebc_workspace_bytes(long long C, int T, int Y, int X);
+int ebc_select_host(int n, int k, const double *E, const double *S, double s_min, int *choice,
+                    double *total_error, long long *nodes);
 int launch_ubench_mfma(const void *a, const void *b, int n_wg, int iters, float *sink,
                        hipStream_t st);
 int launch_ubench_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
