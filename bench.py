@@ -400,13 +400,21 @@ def main():
 
     # ---- untimed replay of the same K steps to count kept-block FLOPs and refresh ratio ----
     has.zero_(); kcnt.zero_()
-    flops, dens, refr = [], [], []
+    flops, dens, refr, ious = [], [], [], []
+    dens_head = torch.zeros(H, device=dev)
+    prev_mask = None
     for it in range(K):
         one_step(it)
         torch.cuda.synchronize()
         flops.append(kept_flops(kidx, kcnt, N, blk, D))
         dens.append(float(kcnt.sum().item()) / (B * H * Nb * Nb))
+        dens_head += kcnt.float().sum(dim=(0, 2)) / (B * Nb * Nb)
         refr.append(float(refresh.float().mean().item()))
+        if prev_mask is not None and it % S != 0:
+            inter = (mask & prev_mask).sum().item()
+            union = (mask | prev_mask).sum().item()
+            ious.append(inter / max(1, union))
+        prev_mask = mask.clone()
     flops_per_step = float(np.mean(flops))
     dense_flops = 4.0 * N * N * D * H * B
 
@@ -445,7 +453,10 @@ def main():
         "attn_kept_tflops": attn_tflops,
         "attn_dense_equiv_tflops": dense_flops / (attn_ms * 1e-3) / 1e12,
         "kept_block_density": float(np.mean(dens)),
+        "kept_block_density_per_head": [round(float(x), 4) for x in (dens_head / K).cpu().tolist()],
         "refreshed_head_fraction": refreshed,
+        "refreshed_head_fraction_per_step": [round(x, 3) for x in refr],
+        "mask_iou_between_consecutive_steps": [round(x, 4) for x in ious],
         "roofline": {
             "kernel": "heart_block_sparse_attn",
             "bound": "mfma",

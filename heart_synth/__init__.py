@@ -23,7 +23,8 @@ Recipe (all configs):
   prepended to the grid tokens.
 
 Multi-step schedules: step s adds, per head, a common offset vector (which is
-what moves the token mean) of scheduled L1 size, plus noise_std[s, h] times one
+what moves the token mean) of scheduled L1 size, directed within the span of the
+head's own sinusoid directions (so that it also changes the head's block scores), plus noise_std[s, h] times one
 fixed iid N(0,1) field per (tensor, head).
 """
 from __future__ import annotations
@@ -224,21 +225,24 @@ class HeartInputGenerator:
             raise ValueError(cfg.schedule)
         self.offset_l1 = np.cumsum(inc, axis=0)  # [S, H]
         self.noise_std = noise
-        # fixed per-head offset directions (unit L1 norm), separate for Q and K
+        # Fixed per-head offset directions (unit L1 norm), separate for Q and K.  They lie in
+        # the span of the head's own field directions: an offset of Q then adds a term to the
+        # logits that varies with the key position, so a head that drifts more also has a
+        # block mask that changes more (the relation TMR relies on, Sec. 4.1-4.2).
         self.dir_q = np.zeros((H, D), dtype=np.float32)
         self.dir_k = np.zeros((H, D), dtype=np.float32)
         for h in range(H):
             r = _head_rng(cfg.seed, 9002, h)
+            _, _, u_qk, _ = self._field_params(h)
             for arr in (self.dir_q, self.dir_k):
-                v = r.standard_normal(D)
+                v = r.standard_normal(4) @ u_qk
                 arr[h] = (v / np.abs(v).sum()).astype(np.float32)
 
     # ---- base fields -----------------------------------------------------------
-    def _field(self, h: int) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
-        cfg = self.cfg
-        T, Hg, W = cfg.grid
-        D = cfg.D
-        rng = _head_rng(cfg.seed, 100, h)
+    def _field_params(self, h: int):
+        """Frequencies, phases and directions of head h's four sinusoids (deterministic)."""
+        D = self.cfg.D
+        rng = _head_rng(self.cfg.seed, 100, h)
         freqs = np.zeros((4, 3), dtype=np.float64)
         # Sinusoids 0..2 vary over (t, y) only, so they survive pooling over a
         # block of consecutive tokens (a block spans whole rows of the grid);
@@ -253,6 +257,13 @@ class HeartInputGenerator:
         phase = rng.uniform(0.0, 2.0 * math.pi, size=4)
         u_qk = rng.standard_normal((4, D)) / math.sqrt(D)  # rows of about unit norm
         u_v = rng.standard_normal((4, D)) / math.sqrt(D)
+        return freqs, phase, u_qk, u_v
+
+    def _field(self, h: int) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+        cfg = self.cfg
+        T, Hg, W = cfg.grid
+        D = cfg.D
+        freqs, phase, u_qk, u_v = self._field_params(h)
         n = np.arange(T * Hg * W)
         t = n // (Hg * W)
         y = (n // W) % Hg

@@ -438,3 +438,35 @@ def test_tiny_config_end_to_end_sanity():
         d, r = oracle.drift(means[1][0], means[1][1], qa, ka, has,
                             np.full(2, delta, np.float32), 0.0, 1.0)
         assert r[0].tolist() == want, (delta, d)
+
+
+def test_drift_and_mask_stability_are_negatively_related():
+    """Sec. 4.1 / 4.2 (the observation TMR rests on): heads whose pooled Q/K features have drifted
+    more from the anchor step have masks that overlap less with the anchor mask.  Sign only:
+    Spearman rank correlation between drift and mask IoU over (head, step) pairs is negative."""
+    import dataclasses
+
+    from scipy.stats import spearmanr
+
+    from heart_synth import CONFIGS, HeartInputGenerator
+
+    cfg = dataclasses.replace(CONFIGS["small_ragged"], name="small_ragged_obs", steps=6, H=6, seed=21)
+    g = HeartInputGenerator(cfg)
+    st0 = g.step(0)
+    qb0, qm0 = oracle.pool(as_u16(st0.q), cfg.block)
+    kb0, km0 = oracle.pool(as_u16(st0.k), cfg.block)
+    m0, _, _ = oracle.topp(oracle.scores(qb0, kb0), g.tau)
+    drifts, ious = [], []
+    for s in range(1, cfg.steps):
+        st = g.step(s)
+        qb, qm = oracle.pool(as_u16(st.q), cfg.block)
+        kb, km = oracle.pool(as_u16(st.k), cfg.block)
+        has = np.ones((cfg.B, cfg.H), np.uint8)
+        d, _ = oracle.drift(qm, km, qm0.copy(), km0.copy(), has, g.delta, 0.0, 1.0, commit=False)
+        m, _, _ = oracle.topp(oracle.scores(qb, kb), g.tau)
+        inter = (m & m0).sum(axis=(2, 3)).astype(np.float64)
+        union = (m | m0).sum(axis=(2, 3)).astype(np.float64)
+        drifts.append(d.reshape(-1))
+        ious.append((inter / union).reshape(-1))
+    rho, _ = spearmanr(np.concatenate(drifts), np.concatenate(ious))
+    assert rho < -0.3, rho
