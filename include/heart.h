@@ -9,7 +9,8 @@
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller (for instance the
  *     storage of PyTorch-ROCm tensors).  The library allocates nothing, keeps no
- *     state between calls, reads no environment variable; the one kernel that needs
+ *     state between calls (beyond per-device launch attributes it sets once), reads no
+ *     environment variable; the one kernel that needs
  *     scratch memory takes it as a workspace argument.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call
  *     only enqueues kernels on that stream and returns; it never synchronises.
@@ -167,7 +168,9 @@ size_t heart_attn_workspace_bytes(const heart_shape *shape);
  * heart_ebc_select: the one-candidate-per-head selection of Eq. 5, solved exactly on the
  *   HOST.  error_host, sparsity_host: [n_heads, n_candidates] doubles; minimises the summed
  *   error subject to mean sparsity >= min_mean_sparsity; choice_host: int[n_heads];
- *   total_error_host: double[1].  HEART_EINVAL if the budget cannot be met.
+ *   total_error_host: double[1].  HEART_EINVAL if the budget cannot be met;
+ *   HEART_EUNSUPPORTED if optimality could not be proved within the search limit (the best
+ *   selection found is then in choice_host; not observed on tables of 6400 x 8).
  */
 int heart_ebc_band_error(long long C, int T, int Y, int X, const float *err, const float *dense,
                          const double *weights4_host, double epsilon, void *workspace,

@@ -789,14 +789,16 @@ static int launch_attn_t(const heart_shape &s, const void *q, const void *k, con
   const int BH = s.B * s.H;
   const size_t lds = 4 * (size_t)kStageRows * D * 2;  // >= BLK * (D + 8) * 2 of the output staging
   auto kern = attn_kernel<D, BLK>;
-  static bool attr_set = false;  // the attribute is per function, set once per process
-  if (!attr_set) {
+  const int dev = current_device();
+  if (dev < 0) return fail(HEART_EHIP, "heart_block_sparse_attn: cannot identify the current device");
+  static bool attr_set[kMaxDevices] = {};  // the attribute is per function and device
+  if (!attr_set[dev]) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess)
       return fail(HEART_EHIP, "hipFuncSetAttribute(max dynamic LDS %zu): %s", lds,
                   hipGetErrorString(e));
-    attr_set = true;
+    attr_set[dev] = true;
   }
   const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
   const float scale_log2e = sc * 1.4426950408889634f;
@@ -805,15 +807,14 @@ static int launch_attn_t(const heart_shape &s, const void *q, const void *k, con
   if (order) {
     // persistent workgroups: as many as are resident at once (HEART_ATTN_OCC per SIMD, i.e.
     // two workgroups of four wavefronts per CU)
-    static int n_cu = 0;  // of the device that was current at the first call
-    if (n_cu == 0) {
-      int dev = 0, v = 0;
-      if (hipGetDevice(&dev) != hipSuccess ||
-          hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+    static int n_cu[kMaxDevices] = {};
+    if (n_cu[dev] == 0) {
+      int v = 0;
+      if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
         return fail(HEART_EHIP, "heart_block_sparse_attn: cannot query the number of CUs");
-      n_cu = v;
+      n_cu[dev] = v;
     }
-    const long long resident = (long long)n_cu * HEART_ATTN_OCC * 4 / (BLK / 32);
+    const long long resident = (long long)n_cu[dev] * HEART_ATTN_OCC * 4 / (BLK / 32);
     grid = n_items < resident ? n_items : resident;
   }
   if (grid > 0x7fffffffLL) return fail(HEART_EUNSUPPORTED, "heart_block_sparse_attn: grid too large");
@@ -821,14 +822,14 @@ static int launch_attn_t(const heart_shape &s, const void *q, const void *k, con
     const uint32_t mult = (uint32_t)(((kOrderClasses - 1) << 16) / Nb);
     if (Nb <= kOrderStagedMax) {
       auto okern = attn_order_kernel<true>;
-      static bool order_attr_set = false;
-      if (!order_attr_set) {
+      static bool order_attr_set[kMaxDevices] = {};
+      if (!order_attr_set[dev]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(okern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
                                            kOrderStagedMax);
         if (e != hipSuccess)
           return fail(HEART_EHIP, "hipFuncSetAttribute(order kernel LDS): %s", hipGetErrorString(e));
-        order_attr_set = true;
+        order_attr_set[dev] = true;
       }
       hipLaunchKernelGGL(okern, dim3((unsigned)BH), dim3(256), (size_t)((Nb + 15) / 16 * 16), st,
                          kept_count, BH, Nb, mult, order);

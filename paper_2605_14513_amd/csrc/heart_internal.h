@@ -116,6 +116,14 @@ __device__ __forceinline__ float wave_sum_f32(float v) {
   return v;
 }
 
+// Index of the current device, for per-device caches of launch attributes (-1 on error).
+constexpr int kMaxDevices = 64;
+inline int current_device() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
+  return dev;
+}
+
 // launchers implemented per kernel file
 int launch_pool(const heart_shape &s, const void *q, const void *k, float *qblk, float *kblk,
                 float *qmean, float *kmean, hipStream_t st);

@@ -275,13 +275,15 @@ static int launch_cmax(int B, int H, int Nb, int D, const float *qblk, const flo
   size_t lds = scores_in ? 0 : (size_t)kRows * 64 * CMAX * 4 + (size_t)kRows * (D + 2) * 8;
   long long nwg = (long long)B * H * groups;
   if (lds > 64 * 1024) {
-    static bool attr_set = false;  // per instantiation: the attribute is per function
-    if (!attr_set) {
+    const int dev = current_device();
+    if (dev < 0) return fail(HEART_EHIP, "heart_mask_topp: cannot identify the current device");
+    static bool attr_set[kMaxDevices] = {};  // per instantiation: the attribute is per function and device
+    if (!attr_set[dev]) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(mask_topp_kernel<CMAX>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
       if (e != hipSuccess)
         return fail(HEART_EHIP, "hipFuncSetAttribute(mask kernel LDS): %s", hipGetErrorString(e));
-      attr_set = true;
+      attr_set[dev] = true;
     }
   }
   hipLaunchKernelGGL(mask_topp_kernel<CMAX>, dim3((unsigned)nwg), dim3(64 * kWaves), lds, st, H, Nb, D,
