@@ -413,3 +413,40 @@ def test_chained_steps_match_oracle(heart, name):
         rows_same = np.repeat(same, cfg.block, axis=2)[:, :, :cfg.N]
         err = np.abs(got - oout)[rows_same].max()
         assert err <= ATTN_ATOL, f"step {s}: attention max abs err {err:.4f}"
+
+
+# ------------------------------------------------------------------------------ shapes
+@pytest.mark.parametrize("B,H,N,D,blk", [
+    (1, 1, 33, 128, 128),     # one ragged block, a single head: 7 of the 8 XCD lists are empty
+    (1, 1, 100, 64, 64),      # two blocks, the second ragged
+    (1, 3, 128, 64, 128),     # exactly one full block per head
+    (2, 2, 1, 128, 128),      # a single token
+    (1, 5, 700, 128, 128),    # fewer heads than XCDs
+    (1, 9, 330, 64, 64),      # more heads than XCDs, uneven lists
+    (1, 2, 4100, 64, 128),    # 33 blocks, last one with 4 tokens
+])
+def test_attn_small_and_odd_shapes(heart, B, H, N, D, blk):
+    # random bf16 tensors, random kept lists with duplicates and out-of-order entries;
+    # K/V rows padded (row stride larger than D) to exercise the strides
+    rng = np.random.default_rng(B * 1000 + H * 100 + N)
+    Nb = (N + blk - 1) // blk
+    def rand():
+        full = torch.randn((B, H, N, D + 16), generator=torch.Generator().manual_seed(int(rng.integers(1 << 30)))).to(torch.bfloat16)
+        return full
+    qf_, kf_, vf_ = rand(), rand(), rand()
+    qc, kc, vc = (x[..., :D] for x in (qf_, kf_, vf_))          # CPU views
+    q, k, v = (x.cuda()[..., :D] for x in (qf_, kf_, vf_))       # strided GPU views (token stride D+16)
+    cnt = rng.integers(0, Nb + 1, size=(B, H, Nb)).astype(np.int32)
+    idx = rng.integers(0, Nb, size=(B, H, Nb, Nb)).astype(np.int32)  # duplicates allowed
+    want = oracle.attn(u16(qc.contiguous()), u16(kc.contiguous()), u16(vc.contiguous()), blk, idx, cnt)
+    for ws in ("auto", None):
+        out = torch.full((B, H, N, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        heart.heart_block_sparse_attn(q, k, v, blk, np_gpu(idx), np_gpu(cnt), out=out, workspace=ws)
+        torch.cuda.synchronize()
+        got = out.float().cpu().numpy().astype(np.float64)
+        assert np.isfinite(got).all(), "every output row is written"
+        rows_empty = np.repeat(cnt == 0, blk, axis=2)[:, :, :N]
+        assert np.all(got[rows_empty] == 0.0)  # rows without kept blocks give zeros
+        if (~rows_empty).any():
+            err = np.abs(got - want)[~rows_empty].max()
+            assert err <= ATTN_ATOL, f"workspace={ws}: max abs err {err:.4f}"
