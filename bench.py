@@ -69,9 +69,10 @@ def kept_flops(kept_idx, kept_count, N, block, D):
     return float(4.0 * D * per_row.sum().item())
 
 
-def attn_traffic(workload):
-    """HBM bytes per launch of the attention kernel from the committed rocprofv3 --pmc
-    summary (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size), or None."""
+def attn_profile(workload):
+    """Figures of the attention kernel from the committed rocprofv3 --pmc summary: HBM bytes
+    per launch (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size) and the
+    matrix-pipe, LDS and L2 counters.  Empty when the summary covers another workload."""
     try:
         t = {}
         with open(TRAFFIC_FILE) as f:
@@ -80,10 +81,15 @@ def attn_traffic(workload):
                     key, val = line.split(":", 1)
                     t[key.strip()] = val.strip()
         if t.get("workload") != workload:
-            return None
-        return float(t["fetch_bytes_per_launch"]) + float(t["write_bytes_per_launch"])
+            return {}
+        out = {"traffic": float(t["fetch_bytes_per_launch"]) + float(t["write_bytes_per_launch"])}
+        for key, name in (("mfma_util_percent", "mfma_pipe_busy_frac"), ("lds_util_percent", "lds_busy_frac"),
+                          ("l2_hit_rate_percent", "l2_hit_rate")):
+            if key in t:
+                out[name] = round(float(t[key]) / 100.0, 3)
+        return out
     except (OSError, ValueError, KeyError):
-        return None
+        return {}
 
 
 def measured_ceilings(heart, torch, q0, k0):
@@ -425,6 +431,7 @@ def main():
     mask_bytes = refreshed * B * H * (2 * Nb * D * 4 + Nb * Nb * (1 + 4))
 
     ceil = measured_ceilings(heart, torch, steps_in[0][0], steps_in[0][1])
+    prof = attn_profile(args.workload)
     mask_f64_flops = refreshed * B * H * 2.0 * Nb * Nb * D  # fp64 dot products of the score stage
 
     result = {
@@ -464,7 +471,8 @@ def main():
             "peak": PEAK_BF16_MFMA_TFLOPS,
             "unit": "TFLOP/s",
             "frac": attn_tflops / PEAK_BF16_MFMA_TFLOPS,
-            "traffic": attn_traffic(args.workload),
+            "traffic": prof.get("traffic"),
+            "profiled_counters": {k_: v_ for k_, v_ in prof.items() if k_ != "traffic"} or None,
             # the same kernel against what the matrix cores sustain on this chip, measured in
             # this run by an MFMA-only loop (the clock drops on real data: power limit)
             "measured_mfma_only_tflops": {"zero_operands": ceil["zero_operands"],
