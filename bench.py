@@ -138,9 +138,15 @@ def policy_sweep(args, heart, torch, g, steps_in, tau, delta):
     cfg = g.cfg
     S = len(steps_in)
     res = []
-    for policy in ("always", "heart", "interval:4", "warmup:5"):
+    # the four policies of the ablation, then the drift-threshold sweep: the paper sweeps
+    # delta over {0, 10, 30, 100} with 30 its operating point; here the same ratios to the
+    # synthetic operating point (delta = 0 refreshes every head whose features moved at all)
+    variants = [("always", "always", 1.0), ("heart", "heart", 1.0), ("interval:4", "interval:4", 1.0),
+                ("warmup:5", "warmup:5", 1.0), ("heart, delta x 0", "heart", 0.0),
+                ("heart, delta x 1/3", "heart", 1.0 / 3.0), ("heart, delta x 10/3", "heart", 10.0 / 3.0)]
+    for label, policy, dscale in variants:
         drv = TmrDriver(TmrConfig(B=cfg.B, H=cfg.H, N=cfg.N, D=cfg.D, block=cfg.block, tau=tau,
-                                  delta=delta, policy=policy, dense_steps=5,
+                                  delta=delta * dscale, policy=policy, dense_steps=5,
                                   n_always_kv_blocks=cfg.n_text_blocks,
                                   n_dense_q_blocks=cfg.n_text_blocks),
                         n_layers=args.sweep_layers, n_branches=2, record=True, time_kernels=True)
@@ -155,9 +161,10 @@ def policy_sweep(args, heart, torch, g, steps_in, tau, delta):
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         summ = drv.summary()
+        summ["policy"] = label
         summ["wall_ms_per_call"] = wall * 1e3 / summ["calls"]
         res.append(summ)
-        print(f"[bench] policy {policy}: {summ}", file=sys.stderr, flush=True)
+        print(f"[bench] policy {label}: {summ}", file=sys.stderr, flush=True)
         del drv
     return {"metric": "TMR policy sweep (cost only), " + cfg.name, "layers": args.sweep_layers,
             "branches": 2, "steps": args.sweep_steps, "dense_steps": 5, "policies": res,

@@ -16,3 +16,4 @@ from .heart_oracle import (  # noqa: F401
     num_threads,
 )
 from . import ebc_oracle  # noqa: F401
+from . import antidiag_oracle  # noqa: F401
