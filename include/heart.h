@@ -125,6 +125,28 @@ int heart_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float 
                     void *stream);
 
 /*
+ * An alternative importance estimator for heart_mask_topp's scores_in argument: block
+ * scores from strided antidiagonal sums of Q K^T.  The paper leaves importance ranking to
+ * the sparse-attention backbone and names this family by its setting (antidiagonal scoring
+ * with stride 16 on blocks of 128 tokens, appendix on baseline configurations) without
+ * defining it; what this entry point computes is, with S = stride, block = 8 S,
+ * M = ceil(N / S) and tokens past N counted as zero vectors:
+ *   L[a,b]     = 1 / (S sqrt(D)) * sum_{r<S} q[S a + S-1-r] . k[S b + r]     (a, b < M)
+ *   P[a,:]     = softmax_b L[a,:]
+ *   score[I,J] = mean over the reduced queries a of block I of sum_{b in block J} P[a,b]
+ * (bf16 products on the matrix cores, fp32 accumulation and exponentials).  Every row of
+ * `scores` sums to one up to rounding and every entry lies in [0,1].
+ * q, k: bf16 with the strides of `shape` (v/o strides are ignored); scores: fp32
+ * [B,H,Nb,Nb], written in full; workspace: device memory of at least
+ * heart_scores_antidiag_workspace_bytes(shape, stride) bytes, 16-byte aligned, contents
+ * irrelevant on entry and undefined on return; calls that share a workspace must be
+ * stream-ordered.  Supported: block == 8 * stride, Nb <= HEART_MAX_NB, D in {64, 128}.
+ */
+size_t heart_scores_antidiag_workspace_bytes(const heart_shape *shape, int stride);
+int heart_scores_antidiag(const heart_shape *shape, const void *q, const void *k, int stride,
+                          float *scores, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Block-sparse attention consuming the mask as per-row kept-block lists
  * (the sparse attention the mask is produced for; interaction scale from the
  * appendix on query-key stability).

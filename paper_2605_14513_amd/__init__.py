@@ -14,6 +14,8 @@ from .binding import (  # noqa: F401
     heart_last_error,
     heart_mask_topp,
     heart_pool_qk,
+    heart_scores_antidiag,
+    heart_scores_antidiag_workspace_bytes,
     heart_ubench_copy,
     heart_ubench_mfma_bf16,
     heart_version,

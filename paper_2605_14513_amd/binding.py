@@ -75,6 +75,10 @@ def load_library() -> ctypes.CDLL:
     lib.heart_ebc_workspace_bytes.restype = ctypes.c_size_t
     lib.heart_ebc_select.argtypes = [ci, ci, vp, vp, ctypes.c_double, vp, vp]
     lib.heart_ebc_select.restype = ci
+    lib.heart_scores_antidiag.argtypes = [sp, vp, vp, ci, vp, vp, ctypes.c_size_t, vp]
+    lib.heart_scores_antidiag.restype = ci
+    lib.heart_scores_antidiag_workspace_bytes.argtypes = [sp, ci]
+    lib.heart_scores_antidiag_workspace_bytes.restype = ctypes.c_size_t
     lib.heart_last_error.restype = ctypes.c_char_p
     _lib = lib
     return lib
@@ -284,6 +288,40 @@ def heart_ubench_copy(src, dst):
     rc = lib.heart_ubench_copy(_dev(src, src.dtype, "src"), _dev(dst, dst.dtype, "dst"), nbytes, _stream())
     _check("heart_ubench_copy", rc)
     return 2.0 * nbytes
+
+
+def heart_scores_antidiag_workspace_bytes(q, block: int, stride: int) -> int:
+    """Bytes of workspace heart_scores_antidiag needs for tensors shaped like q."""
+    return int(load_library().heart_scores_antidiag_workspace_bytes(
+        ctypes.byref(make_shape(q, q, block)), int(stride)))
+
+
+def heart_scores_antidiag(q, k, block: int, stride: int, scores=None, workspace=None):
+    """Antidiagonal-style block scores fp32 [B,H,Nb,Nb] of bf16 q, k ([B,H,N,D] views), for
+    heart_mask_topp(scores_in=...).  workspace: a contiguous GPU tensor of at least
+    heart_scores_antidiag_workspace_bytes, or None (a fresh tensor from torch's allocator)."""
+    lib = load_library()
+    if q.shape != k.shape:
+        raise ValueError("q and k must have the same shape")
+    B, H, N, D = q.shape
+    Nb = (N + block - 1) // block
+    shape = make_shape(q, k, block)
+    need = int(lib.heart_scores_antidiag_workspace_bytes(ctypes.byref(shape), int(stride)))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous GPU tensor")
+    if scores is None:
+        scores = torch.empty((B, H, Nb, Nb), dtype=torch.float32, device=q.device)
+    elif tuple(scores.shape) != (B, H, Nb, Nb):
+        raise ValueError("scores must be [B,H,Nb,Nb]")
+    rc = lib.heart_scores_antidiag(ctypes.byref(shape), _dev(q, torch.bfloat16, "q", False),
+                                   _dev(k, torch.bfloat16, "k", False), int(stride),
+                                   _dev(scores, torch.float32, "scores"),
+                                   ctypes.c_void_p(workspace.data_ptr()),
+                                   workspace.numel() * workspace.element_size(), _stream())
+    _check("heart_scores_antidiag", rc)
+    return scores
 
 
 def heart_ebc_workspace_bytes(C: int, T: int, Y: int, X: int) -> int:

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libheart.so")
 SOURCES = ["heart_api.hip", "pool_qk.hip", "drift.hip", "mask_topp.hip", "block_sparse_attn.hip",
-           "ubench.hip", "ebc.hip"]
+           "ubench.hip", "ebc.hip", "antidiag_scores.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",

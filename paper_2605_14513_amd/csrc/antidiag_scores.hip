@@ -1,0 +1,305 @@
+// heart_scores_antidiag: an antidiagonal-style block-importance estimator that feeds
+// heart_mask_topp through its scores_in argument, as an alternative to the pooled scores.
+// The paper leaves importance ranking to the sparse-attention backbone and names this
+// family with its setting (antidiagonal scoring, stride 16, blocks of 128 tokens: appendix
+// on baseline configurations); the definition implemented here is
+//   S = stride, block = 8 S, tokens past N are zero vectors,
+//   L[a,b]  = 1/(S sqrt(D)) * sum_{r<S} q[S a + S-1-r] . k[S b + r]   (the antidiagonal of
+//             the S x S tile (a,b) of Q K^T), a, b < M = ceil(N/S)
+//   P[a,:]  = softmax_b L[a,:]
+//   score[I,J] = mean_{a in block I} sum_{b in block J} P[a,b]
+//
+// L is one bf16 GEMM per head: row a of the left operand is the S token rows of reduced
+// query a in reverse order, S*D contiguous-by-row elements, row b of the right operand the
+// S token rows of reduced key b in order.  2 M^2 S D FLOP per head on the matrix cores
+// (v_mfma_f32_32x32x16_bf16), MFMA-bound.
+//
+// Kernel 1 (antidiag_tile): one workgroup (4 wavefronts) per 128 x 128 tile of L.  The
+//   contraction runs in stages of 64 elements (half a token row at D = 128): both operand
+//   tiles go global -> registers -> LDS (16-byte chunks XOR-swizzled by row so that the
+//   fragment reads are conflict free), double-buffered, one barrier per stage, the loads of
+//   the next stage in flight during the MFMAs of the current one.  Wavefront w owns 32
+//   reduced queries against all 128 reduced keys of the tile (S^T layout: keys along the
+//   accumulator rows), so a query's maximum over the tile is a per-lane reduction plus one
+//   exchange with the partner lane.  The epilogue writes, per reduced query, the tile
+//   maximum m and the 16 sums over 8 keys of exp2(L - m): tiles are independent.
+// Kernel 2 (antidiag_combine): one workgroup per query block: global maximum and
+//   normaliser of each of its reduced queries from the tile records, then the mean over the
+//   reduced queries of the rescaled key-block sums.
+#include "heart_internal.h"
+
+namespace heart {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) uint32_t ad_u32x4;
+typedef __attribute__((ext_vector_type(8))) __bf16 ad_bf16x8;
+typedef __attribute__((ext_vector_type(16))) float ad_f32x16;
+union AdFrag {
+  ad_u32x4 u;
+  ad_bf16x8 v;
+};
+
+constexpr int kAdTile = 128;                     // reduced rows per tile side
+constexpr int kAdRowB = 128;                     // bytes per tile row and stage (64 bf16)
+constexpr int kAdTileB = kAdTile * kAdRowB;      // bytes of one operand tile of one stage
+constexpr int kAdKeysPerBlock = 8;               // reduced keys per key block (block = 8 S)
+constexpr int kAdLds = 4 * kAdTileB;             // two stages x two operands
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t ad_rsrc(const uint16_t *base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(base), 0, (int)bytes, 0x00020000);
+}
+
+}  // namespace
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void antidiag_tile_kernel(
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, long long qsb, long long qsh,
+    long long qsn, long long ksb, long long ksh, long long ksn, int H, int BH, int N, int S, int M,
+    int MT, float scale_log2, float *__restrict__ esum, float *__restrict__ mref) {
+  extern __shared__ __align__(1024) unsigned char smem[];
+  // workgroup -> (head, tile): workgroup ids are dealt round-robin to the 8 XCDs; all tiles
+  // of a head go to one XCD so that its operand rows are shared through that XCD's L2
+  const int tph = MT * MT;
+  const long long slot = blockIdx.x / 8;
+  const int bh = (int)(blockIdx.x % 8) + 8 * (int)(slot / tph);
+  if (bh >= BH) return;
+  const int tile = (int)(slot % tph);
+  const int tq = tile / MT, tk = tile % MT;
+  const int b = bh / H, h = bh % H;
+
+  const int t = threadIdx.x;
+  const int lane = t & 63, wave = t >> 6;
+  const int l32 = lane & 31, hf = lane >> 5;
+
+  const __amdgpu_buffer_rsrc_t q_rs = ad_rsrc(q + b * qsb + h * qsh, (uint32_t)((long long)N * qsn * 2));
+  const __amdgpu_buffer_rsrc_t k_rs = ad_rsrc(k + b * ksb + h * ksh, (uint32_t)((long long)N * ksn * 2));
+
+  // staging: thread t moves chunk c = t % 8 of rows t / 8 + 32 p, p = 0..3, of both tiles.
+  // Rows of tokens >= N are out of range for the descriptor and arrive as zeros.
+  const int c = t & 7, row0 = t >> 3;
+  constexpr int SPR = D / 64;  // stages per token row
+  uint32_t q_base[4], k_base[4], lds_w[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int row = row0 + 32 * p;
+    // (token index of sub-row 0; the stage adds its sub-row)
+    q_base[p] = (uint32_t)(S * (kAdTile * tq + row)) * (uint32_t)(qsn * 2) + (uint32_t)c * 16u;
+    k_base[p] = (uint32_t)(S * (kAdTile * tk + row)) * (uint32_t)(ksn * 2) + (uint32_t)c * 16u;
+    lds_w[p] = (uint32_t)(row * kAdRowB + ((c ^ ((row >> 1) & 7)) * 16));
+  }
+  ad_u32x4 ra[4], rb[4];
+  auto load_stage = [&](int st) __attribute__((always_inline)) {
+    const int r = st / SPR, d0 = (st % SPR) * 64;
+    const uint32_t qo = (uint32_t)(S - 1 - r) * (uint32_t)(qsn * 2) + (uint32_t)d0 * 2u;
+    const uint32_t ko = (uint32_t)r * (uint32_t)(ksn * 2) + (uint32_t)d0 * 2u;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      ra[p] = __builtin_amdgcn_raw_buffer_load_b128(k_rs, k_base[p] + ko, 0, 0);
+      rb[p] = __builtin_amdgcn_raw_buffer_load_b128(q_rs, q_base[p] + qo, 0, 0);
+    }
+  };
+  auto store_stage = [&](int buf) __attribute__((always_inline)) {
+    unsigned char *A = smem + buf * 2 * kAdTileB, *B = A + kAdTileB;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      *reinterpret_cast<ad_u32x4 *>(A + lds_w[p]) = ra[p];
+      *reinterpret_cast<ad_u32x4 *>(B + lds_w[p]) = rb[p];
+    }
+  };
+  // fragment of contraction step ks (16 elements) of tile row 32 x + l32: chunk 2 ks + hf
+  uint32_t foff[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) foff[ks] = (uint32_t)(l32 * kAdRowB + (((2 * ks + hf) ^ ((l32 >> 1) & 7)) * 16));
+
+  ad_f32x16 acc[4];
+#pragma unroll
+  for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[kt][r] = 0.f;
+
+  const int n_stages = S * SPR;
+  load_stage(0);
+  store_stage(0);
+  __syncthreads();
+  for (int st = 0; st < n_stages; ++st) {
+    const int buf = st & 1;
+    if (st + 1 < n_stages) load_stage(st + 1);
+    const unsigned char *A = smem + buf * 2 * kAdTileB, *B = A + kAdTileB;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      AdFrag fb;
+      fb.u = *reinterpret_cast<const ad_u32x4 *>(B + wave * 32 * kAdRowB + foff[ks]);
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt) {
+        AdFrag fa;
+        fa.u = *reinterpret_cast<const ad_u32x4 *>(A + kt * 32 * kAdRowB + foff[ks]);
+        acc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, fb.v, acc[kt], 0, 0, 0);
+      }
+    }
+    // the other buffer was last read in the previous iteration, before its closing barrier
+    if (st + 1 < n_stages) store_stage(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: tile maximum and per-key-block sums of this lane's reduced query ---------
+  // accumulator element r of tile kt: reduced key 128 tk + 32 kt + 8 (r / 4) + 4 hf + r % 4
+  const float ninf = -__builtin_inff();
+  float m = ninf;
+#pragma unroll
+  for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int key = kAdTile * tk + 32 * kt + 8 * (r >> 2) + 4 * hf + (r & 3);
+      const float x = key < M ? acc[kt][r] * scale_log2 : ninf;
+      acc[kt][r] = x;
+      m = fmaxf(m, x);
+    }
+  {
+    uint32_t s0, s1;
+    swap_halves32(__float_as_uint(m), s0, s1);
+    m = fmaxf(__uint_as_float(s0), __uint_as_float(s1));
+  }
+  // (every tile holds at least one real key, so m is finite)
+  float sums[4][4];
+#pragma unroll
+  for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      float s = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) s += __builtin_amdgcn_exp2f(acc[kt][4 * g + i] - m);
+      uint32_t s0, s1;
+      swap_halves32(__float_as_uint(s), s0, s1);
+      sums[kt][g] = __uint_as_float(s0) + __uint_as_float(s1);
+    }
+  const int a = kAdTile * tq + 32 * wave + l32;
+  if (a < M) {
+    const int NbP = 16 * MT;
+    float *dst = esum + ((size_t)bh * M + a) * NbP + 16 * tk + 8 * hf;
+    // lower-half lanes write key blocks 0..7 of the tile, upper-half lanes 8..15
+    *reinterpret_cast<float4 *>(dst) = hf ? make_float4(sums[2][0], sums[2][1], sums[2][2], sums[2][3])
+                                          : make_float4(sums[0][0], sums[0][1], sums[0][2], sums[0][3]);
+    *reinterpret_cast<float4 *>(dst + 4) = hf ? make_float4(sums[3][0], sums[3][1], sums[3][2], sums[3][3])
+                                              : make_float4(sums[1][0], sums[1][1], sums[1][2], sums[1][3]);
+    if (hf == 0) mref[((size_t)bh * M + a) * MT + tk] = m;
+  }
+}
+
+// One workgroup (256 lanes) per (head, query block).  Lane t owns key blocks t, t + 256, ...
+__global__ __launch_bounds__(256) void antidiag_combine_kernel(int Nb, int M, int MT,
+                                                              const float *__restrict__ esum,
+                                                              const float *__restrict__ mref,
+                                                              float *__restrict__ scores) {
+  constexpr int RQ = kAdKeysPerBlock;  // reduced queries per query block
+  constexpr int JPT = HEART_MAX_NB / 256;
+  __shared__ float s_m[RQ];
+  __shared__ float s_part[RQ][4];
+  const int I = blockIdx.x % Nb;
+  const long long bh = blockIdx.x / Nb;
+  const int NbP = 16 * MT;
+  const int a0 = I * RQ;
+  const int na = min(RQ, M - a0);
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  // global maximum of each reduced query over its tile records (MT <= 64: one wavefront
+  // per pair of rows)
+  for (int rr = wave; rr < na; rr += 4) {
+    float m = lane < MT ? mref[((size_t)bh * M + a0 + rr) * MT + lane] : -__builtin_inff();
+    m = wave_max_f32(m);
+    if (lane == 0) s_m[rr] = m;
+  }
+  __syncthreads();
+  float w[RQ][JPT];
+#pragma unroll
+  for (int rr = 0; rr < RQ; ++rr) {
+    float part = 0.f;
+#pragma unroll
+    for (int u = 0; u < JPT; ++u) {
+      const int J = t + 256 * u;
+      float x = 0.f;
+      if (rr < na && J < NbP) {
+        const size_t row = (size_t)bh * M + a0 + rr;
+        x = esum[row * NbP + J] * __builtin_amdgcn_exp2f(mref[row * MT + (J >> 4)] - s_m[rr]);
+      }
+      w[rr][u] = x;
+      part += x;
+    }
+    part = wave_sum_f32(part);
+    if (lane == 0) s_part[rr][wave] = part;
+  }
+  __syncthreads();
+  float inv[RQ];
+#pragma unroll
+  for (int rr = 0; rr < RQ; ++rr) {
+    const float l = (s_part[rr][0] + s_part[rr][1]) + (s_part[rr][2] + s_part[rr][3]);
+    inv[rr] = rr < na ? 1.f / l : 0.f;
+  }
+  const float inv_na = 1.f / (float)na;
+#pragma unroll
+  for (int u = 0; u < JPT; ++u) {
+    const int J = t + 256 * u;
+    if (J < Nb) {
+      float s = 0.f;
+#pragma unroll
+      for (int rr = 0; rr < RQ; ++rr) s += w[rr][u] * inv[rr];
+      scores[((size_t)bh * Nb + I) * Nb + J] = s * inv_na;
+    }
+  }
+}
+
+size_t antidiag_workspace_bytes(const heart_shape &s, int stride) {
+  const size_t M = ((size_t)s.N + stride - 1) / stride;
+  const size_t MT = (M + kAdTile - 1) / kAdTile;
+  return (size_t)s.B * s.H * M * (16 * MT + MT) * sizeof(float);
+}
+
+int launch_antidiag(const heart_shape &s, const void *q, const void *k, int stride, float *scores,
+                    float *workspace, hipStream_t st) {
+  const int S = stride;
+  const int M = (s.N + S - 1) / S;
+  const int MT = (M + kAdTile - 1) / kAdTile;
+  const int Nb = (s.N + s.block - 1) / s.block;
+  const int BH = s.B * s.H;
+  // the kernel addresses one head's rows through 32-bit buffer offsets, up to the end of
+  // the last tile
+  const long long rows = (long long)S * kAdTile * MT + S;
+  if (rows * s.q_stride[2] * 2 > 0xffffffffLL || rows * s.k_stride[2] * 2 > 0xffffffffLL)
+    return fail(HEART_EUNSUPPORTED,
+                "heart_scores_antidiag: (N + 129 * stride) * token stride * 2 bytes must stay below 4 GiB");
+  const long long grid = (long long)((BH + 7) / 8) * 8 * MT * MT;
+  if (grid > 0x7fffffffLL || (long long)BH * Nb > 0x7fffffffLL)
+    return fail(HEART_EUNSUPPORTED, "heart_scores_antidiag: grid too large");
+  float *esum = workspace;
+  float *mref = workspace + (size_t)BH * M * 16 * MT;
+  const float scale_log2 = 1.4426950408889634f / ((float)S * sqrtf((float)s.D));
+  const int dev = current_device();
+  if (dev < 0) return fail(HEART_EHIP, "heart_scores_antidiag: cannot identify the current device");
+#define HEART_AD_LAUNCH(DD)                                                                        \
+  do {                                                                                             \
+    auto kern = antidiag_tile_kernel<DD>;                                                          \
+    static bool attr_set[kMaxDevices] = {};                                                        \
+    if (!attr_set[dev]) {                                                                          \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                     \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, kAdLds);      \
+      if (e != hipSuccess)                                                                         \
+        return fail(HEART_EHIP, "hipFuncSetAttribute(antidiagonal tile kernel LDS): %s",           \
+                    hipGetErrorString(e));                                                         \
+      attr_set[dev] = true;                                                                        \
+    }                                                                                              \
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), kAdLds, st, (const uint16_t *)q,     \
+                       (const uint16_t *)k, s.q_stride[0], s.q_stride[1], s.q_stride[2],           \
+                       s.k_stride[0], s.k_stride[1], s.k_stride[2], s.H, BH, s.N, S, M, MT,        \
+                       scale_log2, esum, mref);                                                    \
+  } while (0)
+  if (s.D == 128)
+    HEART_AD_LAUNCH(128);
+  else
+    HEART_AD_LAUNCH(64);
+#undef HEART_AD_LAUNCH
+  if (int rc = check_launch("antidiag_tile_kernel")) return rc;
+  hipLaunchKernelGGL(antidiag_combine_kernel, dim3((unsigned)((long long)BH * Nb)), dim3(256), 0, st, Nb,
+                     M, MT, esum, mref, scores);
+  return check_launch("antidiag_combine_kernel");
+}
+
+}  // namespace heart

@@ -155,6 +155,39 @@ size_t heart_attn_workspace_bytes(const heart_shape *s) {
   return ((size_t)s->B * s->H * (nb + 2) + 24) * sizeof(int);
 }
 
+static int check_antidiag(const heart_shape *s, int stride, const char *fn) {
+  if (int rc = check_shape(s, fn)) return rc;
+  if (stride <= 0 || s->block != 8 * stride)
+    return fail(HEART_EUNSUPPORTED, "%s: block must be 8 * stride (got block %d, stride %d)", fn,
+                s->block, stride);
+  const long long nb = ((long long)s->N + s->block - 1) / s->block;
+  if (nb > HEART_MAX_NB)
+    return fail(HEART_EUNSUPPORTED, "%s: Nb = %lld exceeds HEART_MAX_NB = %d", fn, nb, HEART_MAX_NB);
+  return HEART_OK;
+}
+
+size_t heart_scores_antidiag_workspace_bytes(const heart_shape *s, int stride) {
+  if (!s || s->B <= 0 || s->H <= 0 || s->N <= 0 || stride <= 0) return 0;
+  return antidiag_workspace_bytes(*s, stride);
+}
+
+int heart_scores_antidiag(const heart_shape *shape, const void *q, const void *k, int stride,
+                          float *scores, void *workspace, size_t workspace_bytes, void *stream) {
+  clear_error();
+  if (int rc = check_antidiag(shape, stride, "heart_scores_antidiag")) return rc;
+  if (!q || !k || !scores || !workspace)
+    return fail(HEART_EINVAL, "heart_scores_antidiag: NULL pointer argument");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(workspace))
+    return fail(HEART_EUNSUPPORTED, "heart_scores_antidiag: q, k and workspace must be 16-byte aligned");
+  if (!stride_ok(shape->q_stride) || !stride_ok(shape->k_stride))
+    return fail(HEART_EUNSUPPORTED,
+                "heart_scores_antidiag: strides must be multiples of 8 elements, token stride > 0");
+  if (workspace_bytes < heart_scores_antidiag_workspace_bytes(shape, stride))
+    return fail(HEART_EINVAL, "heart_scores_antidiag: workspace of %zu bytes, need %zu", workspace_bytes,
+                heart_scores_antidiag_workspace_bytes(shape, stride));
+  return launch_antidiag(*shape, q, k, stride, scores, (float *)workspace, (hipStream_t)stream);
+}
+
 int heart_ebc_band_error(long long C, int T, int Y, int X, const float *err, const float *dense,
                          const double *weights4_host, double epsilon, void *workspace,
                          size_t workspace_bytes, double *out6, void *stream) {
