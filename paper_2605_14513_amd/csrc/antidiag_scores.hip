@@ -14,15 +14,16 @@
 // S token rows of reduced key b in order.  2 M^2 S D FLOP per head on the matrix cores
 // (v_mfma_f32_32x32x16_bf16), MFMA-bound.
 //
-// Kernel 1 (antidiag_tile): one workgroup (4 wavefronts) per 128 x 128 tile of L.  The
+// Kernel 1 (antidiag_tile): one workgroup (8 wavefronts) per 256 x 256 tile of L (128 FLOP
+//   per operand byte, which keeps the operand stream from L2 below what it delivers).  The
 //   contraction runs in stages of 64 elements (half a token row at D = 128): both operand
 //   tiles go global -> registers -> LDS (16-byte chunks XOR-swizzled by row so that the
-//   fragment reads are conflict free), double-buffered, one barrier per stage, the loads of
-//   the next stage in flight during the MFMAs of the current one.  Wavefront w owns 32
-//   reduced queries against all 128 reduced keys of the tile (S^T layout: keys along the
-//   accumulator rows), so a query's maximum over the tile is a per-lane reduction plus one
-//   exchange with the partner lane.  The epilogue writes, per reduced query, the tile
-//   maximum m and the 16 sums over 8 keys of exp2(L - m): tiles are independent.
+//   fragment reads are conflict free), double-buffered (128 KB), one barrier per stage, the
+//   loads of the next stage in flight during the MFMAs of the current one.  A wavefront owns
+//   64 reduced queries against 128 reduced keys (S^T layout: keys along the accumulator
+//   rows), so a query's maximum over those keys is a per-lane reduction plus one exchange
+//   with the partner lane.  The epilogue writes one record per (reduced query, 128 keys):
+//   the maximum m and the 16 sums over 8 keys of exp2(L - m).  Tiles are independent.
 // Kernel 2 (antidiag_combine): one workgroup per query block: global maximum and
 //   normaliser of each of its reduced queries from the tile records, then the mean over the
 //   reduced queries of the rescaled key-block sums.
@@ -40,11 +41,11 @@ union AdFrag {
   ad_bf16x8 v;
 };
 
-constexpr int kAdTile = 128;                     // reduced rows per tile side
+constexpr int kAdTile = 256;                     // reduced rows per tile side
 constexpr int kAdRowB = 128;                     // bytes per tile row and stage (64 bf16)
 constexpr int kAdTileB = kAdTile * kAdRowB;      // bytes of one operand tile of one stage
 constexpr int kAdKeysPerBlock = 8;               // reduced keys per key block (block = 8 S)
-constexpr int kAdLds = 4 * kAdTileB;             // two stages x two operands
+constexpr int kAdLds = 4 * kAdTileB;             // two stages x two operands (128 KB)
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t ad_rsrc(const uint16_t *base, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(base), 0, (int)bytes, 0x00020000);
@@ -53,36 +54,38 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t ad_rsrc(const uint16_t *base, 
 }  // namespace
 
 template <int D>
-__global__ __launch_bounds__(256, 2) void antidiag_tile_kernel(
+__global__ __launch_bounds__(512, 2) void antidiag_tile_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, long long qsb, long long qsh,
     long long qsn, long long ksb, long long ksh, long long ksn, int H, int BH, int N, int S, int M,
-    int MT, float scale_log2, float *__restrict__ esum, float *__restrict__ mref) {
+    int MT2, float scale_log2, float *__restrict__ esum, float *__restrict__ mref) {
   extern __shared__ __align__(1024) unsigned char smem[];
   // workgroup -> (head, tile): workgroup ids are dealt round-robin to the 8 XCDs; all tiles
   // of a head go to one XCD so that its operand rows are shared through that XCD's L2
-  const int tph = MT * MT;
+  const int tph = MT2 * MT2;
   const long long slot = blockIdx.x / 8;
   const int bh = (int)(blockIdx.x % 8) + 8 * (int)(slot / tph);
   if (bh >= BH) return;
   const int tile = (int)(slot % tph);
-  const int tq = tile / MT, tk = tile % MT;
+  const int tq = tile / MT2, tk = tile % MT2;
   const int b = bh / H, h = bh % H;
 
   const int t = threadIdx.x;
   const int lane = t & 63, wave = t >> 6;
   const int l32 = lane & 31, hf = lane >> 5;
+  const int wi = wave >> 2;  // which 128 keys of the tile
+  const int wj = wave & 3;   // which 64 queries of the tile
 
   const __amdgpu_buffer_rsrc_t q_rs = ad_rsrc(q + b * qsb + h * qsh, (uint32_t)((long long)N * qsn * 2));
   const __amdgpu_buffer_rsrc_t k_rs = ad_rsrc(k + b * ksb + h * ksh, (uint32_t)((long long)N * ksn * 2));
 
-  // staging: thread t moves chunk c = t % 8 of rows t / 8 + 32 p, p = 0..3, of both tiles.
+  // staging: thread t moves chunk c = t % 8 of rows t / 8 + 64 p, p = 0..3, of both tiles.
   // Rows of tokens >= N are out of range for the descriptor and arrive as zeros.
   const int c = t & 7, row0 = t >> 3;
   constexpr int SPR = D / 64;  // stages per token row
   uint32_t q_base[4], k_base[4], lds_w[4];
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
-    const int row = row0 + 32 * p;
+    const int row = row0 + 64 * p;
     // (token index of sub-row 0; the stage adds its sub-row)
     q_base[p] = (uint32_t)(S * (kAdTile * tq + row)) * (uint32_t)(qsn * 2) + (uint32_t)c * 16u;
     k_base[p] = (uint32_t)(S * (kAdTile * tk + row)) * (uint32_t)(ksn * 2) + (uint32_t)c * 16u;
@@ -112,11 +115,13 @@ __global__ __launch_bounds__(256, 2) void antidiag_tile_kernel(
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) foff[ks] = (uint32_t)(l32 * kAdRowB + (((2 * ks + hf) ^ ((l32 >> 1) & 7)) * 16));
 
-  ad_f32x16 acc[4];
+  ad_f32x16 acc[4][2];
 #pragma unroll
   for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[kt][r] = 0.f;
+    for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[kt][qt][r] = 0.f;
 
   const int n_stages = S * SPR;
   load_stage(0);
@@ -125,16 +130,21 @@ __global__ __launch_bounds__(256, 2) void antidiag_tile_kernel(
   for (int st = 0; st < n_stages; ++st) {
     const int buf = st & 1;
     if (st + 1 < n_stages) load_stage(st + 1);
-    const unsigned char *A = smem + buf * 2 * kAdTileB, *B = A + kAdTileB;
+    const unsigned char *A = smem + buf * 2 * kAdTileB + wi * 128 * kAdRowB;
+    const unsigned char *B = smem + buf * 2 * kAdTileB + kAdTileB + wj * 64 * kAdRowB;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      AdFrag fb;
-      fb.u = *reinterpret_cast<const ad_u32x4 *>(B + wave * 32 * kAdRowB + foff[ks]);
+      AdFrag fb[2];
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt)
+        fb[qt].u = *reinterpret_cast<const ad_u32x4 *>(B + qt * 32 * kAdRowB + foff[ks]);
 #pragma unroll
       for (int kt = 0; kt < 4; ++kt) {
         AdFrag fa;
         fa.u = *reinterpret_cast<const ad_u32x4 *>(A + kt * 32 * kAdRowB + foff[ks]);
-        acc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, fb.v, acc[kt], 0, 0, 0);
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt)
+          acc[kt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, fb[qt].v, acc[kt][qt], 0, 0, 0);
       }
     }
     // the other buffer was last read in the previous iteration, before its closing barrier
@@ -142,47 +152,53 @@ __global__ __launch_bounds__(256, 2) void antidiag_tile_kernel(
     __syncthreads();
   }
 
-  // ---- epilogue: tile maximum and per-key-block sums of this lane's reduced query ---------
-  // accumulator element r of tile kt: reduced key 128 tk + 32 kt + 8 (r / 4) + 4 hf + r % 4
+  // ---- epilogue: record of (reduced query, 128 keys): maximum and 16 key-block sums ----------
+  // accumulator element r of key tile kt: reduced key key0 + 32 kt + 8 (r / 4) + 4 hf + r % 4
   const float ninf = -__builtin_inff();
-  float m = ninf;
+  const int key0 = kAdTile * tk + 128 * wi;
+  const int rec = 2 * tk + wi;  // index of the 128-key record
+  const int MT = 2 * MT2, NbP = 16 * MT;
 #pragma unroll
-  for (int kt = 0; kt < 4; ++kt)
+  for (int qt = 0; qt < 2; ++qt) {
+    float m = ninf;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int key = kAdTile * tk + 32 * kt + 8 * (r >> 2) + 4 * hf + (r & 3);
-      const float x = key < M ? acc[kt][r] * scale_log2 : ninf;
-      acc[kt][r] = x;
-      m = fmaxf(m, x);
-    }
-  {
-    uint32_t s0, s1;
-    swap_halves32(__float_as_uint(m), s0, s1);
-    m = fmaxf(__uint_as_float(s0), __uint_as_float(s1));
-  }
-  // (every tile holds at least one real key, so m is finite)
-  float sums[4][4];
+    for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-  for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      float s = 0.f;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) s += __builtin_amdgcn_exp2f(acc[kt][4 * g + i] - m);
+      for (int r = 0; r < 16; ++r) {
+        const int key = key0 + 32 * kt + 8 * (r >> 2) + 4 * hf + (r & 3);
+        const float x = key < M ? acc[kt][qt][r] * scale_log2 : ninf;
+        acc[kt][qt][r] = x;
+        m = fmaxf(m, x);
+      }
+    {
       uint32_t s0, s1;
-      swap_halves32(__float_as_uint(s), s0, s1);
-      sums[kt][g] = __uint_as_float(s0) + __uint_as_float(s1);
+      swap_halves32(__float_as_uint(m), s0, s1);
+      m = fmaxf(__uint_as_float(s0), __uint_as_float(s1));
     }
-  const int a = kAdTile * tq + 32 * wave + l32;
-  if (a < M) {
-    const int NbP = 16 * MT;
-    float *dst = esum + ((size_t)bh * M + a) * NbP + 16 * tk + 8 * hf;
-    // lower-half lanes write key blocks 0..7 of the tile, upper-half lanes 8..15
-    *reinterpret_cast<float4 *>(dst) = hf ? make_float4(sums[2][0], sums[2][1], sums[2][2], sums[2][3])
-                                          : make_float4(sums[0][0], sums[0][1], sums[0][2], sums[0][3]);
-    *reinterpret_cast<float4 *>(dst + 4) = hf ? make_float4(sums[3][0], sums[3][1], sums[3][2], sums[3][3])
-                                              : make_float4(sums[1][0], sums[1][1], sums[1][2], sums[1][3]);
-    if (hf == 0) mref[((size_t)bh * M + a) * MT + tk] = m;
+    // (a record whose 128 keys are all past the end has m = -inf and all sums zero)
+    const float mm = m == ninf ? 0.f : m;
+    float sums[4][4];
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s += __builtin_amdgcn_exp2f(acc[kt][qt][4 * g + i] - mm);
+        uint32_t s0, s1;
+        swap_halves32(__float_as_uint(s), s0, s1);
+        sums[kt][g] = __uint_as_float(s0) + __uint_as_float(s1);
+      }
+    const int a = kAdTile * tq + 64 * wj + 32 * qt + l32;
+    if (a < M) {
+      float *dst = esum + ((size_t)bh * M + a) * NbP + 16 * rec + 8 * hf;
+      // lower-half lanes write key blocks 0..7 of the record, upper-half lanes 8..15
+      *reinterpret_cast<float4 *>(dst) = hf ? make_float4(sums[2][0], sums[2][1], sums[2][2], sums[2][3])
+                                            : make_float4(sums[0][0], sums[0][1], sums[0][2], sums[0][3]);
+      *reinterpret_cast<float4 *>(dst + 4) = hf ? make_float4(sums[3][0], sums[3][1], sums[3][2], sums[3][3])
+                                                : make_float4(sums[1][0], sums[1][1], sums[1][2], sums[1][3]);
+      if (hf == 0) mref[((size_t)bh * M + a) * MT + rec] = m;
+    }
   }
 }
 
@@ -249,7 +265,7 @@ __global__ __launch_bounds__(256) void antidiag_combine_kernel(int Nb, int M, in
 
 size_t antidiag_workspace_bytes(const heart_shape &s, int stride) {
   const size_t M = ((size_t)s.N + stride - 1) / stride;
-  const size_t MT = (M + kAdTile - 1) / kAdTile;
+  const size_t MT = 2 * ((M + kAdTile - 1) / kAdTile);  // records of 128 keys per reduced query
   return (size_t)s.B * s.H * M * (16 * MT + MT) * sizeof(float);
 }
 
@@ -257,16 +273,19 @@ int launch_antidiag(const heart_shape &s, const void *q, const void *k, int stri
                     float *workspace, hipStream_t st) {
   const int S = stride;
   const int M = (s.N + S - 1) / S;
-  const int MT = (M + kAdTile - 1) / kAdTile;
+  const int MT2 = (M + kAdTile - 1) / kAdTile;
+  const int MT = 2 * MT2;
   const int Nb = (s.N + s.block - 1) / s.block;
   const int BH = s.B * s.H;
+  if (MT > 64)  // one wavefront reads a reduced query's records in the combine kernel
+    return fail(HEART_EUNSUPPORTED, "heart_scores_antidiag: more than 8192 reduced rows");
   // the kernel addresses one head's rows through 32-bit buffer offsets, up to the end of
   // the last tile
-  const long long rows = (long long)S * kAdTile * MT + S;
+  const long long rows = (long long)S * kAdTile * MT2 + S;
   if (rows * s.q_stride[2] * 2 > 0xffffffffLL || rows * s.k_stride[2] * 2 > 0xffffffffLL)
     return fail(HEART_EUNSUPPORTED,
-                "heart_scores_antidiag: (N + 129 * stride) * token stride * 2 bytes must stay below 4 GiB");
-  const long long grid = (long long)((BH + 7) / 8) * 8 * MT * MT;
+                "heart_scores_antidiag: (N + 257 * stride) * token stride * 2 bytes must stay below 4 GiB");
+  const long long grid = (long long)((BH + 7) / 8) * 8 * MT2 * MT2;
   if (grid > 0x7fffffffLL || (long long)BH * Nb > 0x7fffffffLL)
     return fail(HEART_EUNSUPPORTED, "heart_scores_antidiag: grid too large");
   float *esum = workspace;
@@ -286,9 +305,9 @@ int launch_antidiag(const heart_shape &s, const void *q, const void *k, int stri
                     hipGetErrorString(e));                                                         \
       attr_set[dev] = true;                                                                        \
     }                                                                                              \
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), kAdLds, st, (const uint16_t *)q,     \
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), kAdLds, st, (const uint16_t *)q,     \
                        (const uint16_t *)k, s.q_stride[0], s.q_stride[1], s.q_stride[2],           \
-                       s.k_stride[0], s.k_stride[1], s.k_stride[2], s.H, BH, s.N, S, M, MT,        \
+                       s.k_stride[0], s.k_stride[1], s.k_stride[2], s.H, BH, s.N, S, M, MT2,       \
                        scale_log2, esum, mref);                                                    \
   } while (0)
   if (s.D == 128)
