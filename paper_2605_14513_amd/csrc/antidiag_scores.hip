@@ -91,23 +91,26 @@ __global__ __launch_bounds__(512, 2) void antidiag_tile_kernel(
     k_base[p] = (uint32_t)(S * (kAdTile * tk + row)) * (uint32_t)(ksn * 2) + (uint32_t)c * 16u;
     lds_w[p] = (uint32_t)(row * kAdRowB + ((c ^ ((row >> 1) & 7)) * 16));
   }
-  ad_u32x4 ra[4], rb[4];
-  auto load_stage = [&](int st) __attribute__((always_inline)) {
+  // two register sets: the loads of a stage are issued two stages before its MFMAs and
+  // written to LDS in the middle of the stage before (into the buffer the stage before
+  // that one has released at its closing barrier)
+  ad_u32x4 ra[2][4], rb[2][4];
+  auto load_stage = [&](int set, int st) __attribute__((always_inline)) {
     const int r = st / SPR, d0 = (st % SPR) * 64;
     const uint32_t qo = (uint32_t)(S - 1 - r) * (uint32_t)(qsn * 2) + (uint32_t)d0 * 2u;
     const uint32_t ko = (uint32_t)r * (uint32_t)(ksn * 2) + (uint32_t)d0 * 2u;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      ra[p] = __builtin_amdgcn_raw_buffer_load_b128(k_rs, k_base[p] + ko, 0, 0);
-      rb[p] = __builtin_amdgcn_raw_buffer_load_b128(q_rs, q_base[p] + qo, 0, 0);
+      ra[set][p] = __builtin_amdgcn_raw_buffer_load_b128(k_rs, k_base[p] + ko, 0, 0);
+      rb[set][p] = __builtin_amdgcn_raw_buffer_load_b128(q_rs, q_base[p] + qo, 0, 0);
     }
   };
-  auto store_stage = [&](int buf) __attribute__((always_inline)) {
+  auto store_stage = [&](int set, int buf) __attribute__((always_inline)) {
     unsigned char *A = smem + buf * 2 * kAdTileB, *B = A + kAdTileB;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      *reinterpret_cast<ad_u32x4 *>(A + lds_w[p]) = ra[p];
-      *reinterpret_cast<ad_u32x4 *>(B + lds_w[p]) = rb[p];
+      *reinterpret_cast<ad_u32x4 *>(A + lds_w[p]) = ra[set][p];
+      *reinterpret_cast<ad_u32x4 *>(B + lds_w[p]) = rb[set][p];
     }
   };
   // fragment of contraction step ks (16 elements) of tile row 32 x + l32: chunk 2 ks + hf
@@ -123,17 +126,11 @@ __global__ __launch_bounds__(512, 2) void antidiag_tile_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[kt][qt][r] = 0.f;
 
-  const int n_stages = S * SPR;
-  load_stage(0);
-  store_stage(0);
-  __syncthreads();
-  for (int st = 0; st < n_stages; ++st) {
-    const int buf = st & 1;
-    if (st + 1 < n_stages) load_stage(st + 1);
+  auto mfma_steps = [&](int buf, int ks0) __attribute__((always_inline)) {
     const unsigned char *A = smem + buf * 2 * kAdTileB + wi * 128 * kAdRowB;
     const unsigned char *B = smem + buf * 2 * kAdTileB + kAdTileB + wj * 64 * kAdRowB;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
+    for (int ks = ks0; ks < ks0 + 2; ++ks) {
       AdFrag fb[2];
 #pragma unroll
       for (int qt = 0; qt < 2; ++qt)
@@ -147,8 +144,25 @@ __global__ __launch_bounds__(512, 2) void antidiag_tile_kernel(
           acc[kt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, fb[qt].v, acc[kt][qt], 0, 0, 0);
       }
     }
-    // the other buffer was last read in the previous iteration, before its closing barrier
-    if (st + 1 < n_stages) store_stage(buf ^ 1);
+  };
+
+  const int n_stages = S * SPR;  // even: the stride is 8 or 16
+  load_stage(0, 0);
+  load_stage(1, 1);
+  store_stage(0, 0);
+  __syncthreads();
+  for (int st = 0; st < n_stages; st += 2) {
+    // stage st from buffer 0; register set 0 is free again
+    if (st + 2 < n_stages) load_stage(0, st + 2);
+    mfma_steps(0, 0);
+    store_stage(1, 1);  // stage st + 1; buffer 1 was released by the barrier before this stage
+    mfma_steps(0, 2);
+    __syncthreads();
+    // stage st + 1 from buffer 1
+    if (st + 3 < n_stages) load_stage(1, st + 3);
+    mfma_steps(1, 0);
+    if (st + 2 < n_stages) store_stage(0, 0);
+    mfma_steps(1, 2);
     __syncthreads();
   }
 
