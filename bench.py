@@ -47,6 +47,10 @@ def parse_args():
                     help="instead of the headline step: calibrate per-head thresholds on the workload "
                          "(errors measured with the library's sparse attention on synthetic tensors) "
                          "and print one JSON line comparing them with the shared threshold 0.9")
+    ap.add_argument("--estimator-demo", action="store_true",
+                    help="instead of the headline step: time the antidiagonal-style importance estimator "
+                         "(heart_scores_antidiag -> heart_mask_topp(scores_in)) on the workload, compare its "
+                         "masks with the pooled estimator's and print one JSON line")
     ap.add_argument("--sweep-steps", type=int, default=15)
     ap.add_argument("--sweep-layers", type=int, default=2)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -236,6 +240,56 @@ def ebc_demo(args, heart, torch, g, steps_in):
     }
 
 
+def estimator_demo(args, heart, torch, g, steps_in, tau):
+    """The alternative importance estimator behind heart_mask_topp's scores_in: time of its two
+    kernels, its matrix-core rate, and how its masks compare with the pooled estimator's."""
+    cfg = g.cfg
+    B, H, N, D, Nb, blk, nt = cfg.B, cfg.H, cfg.N, cfg.D, cfg.Nb, cfg.block, cfg.n_text_blocks
+    stride = blk // 8
+    q, k, v = steps_in[0]
+    ws = torch.empty(heart.heart_scores_antidiag_workspace_bytes(q, blk, stride), dtype=torch.uint8, device=q.device)
+    sc = torch.empty((B, H, Nb, Nb), dtype=torch.float32, device=q.device)
+    K, W = max(1, args.steps), max(1, args.warmup)
+    for _ in range(W):
+        heart.heart_scores_antidiag(q, k, blk, stride, scores=sc, workspace=ws)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    for i in range(K):
+        heart.heart_scores_antidiag(*steps_in[i % len(steps_in)][:2], blk, stride, scores=sc, workspace=ws)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(K))
+    M = (N + stride - 1) // stride
+    flops = 2.0 * M * M * stride * D * B * H
+    heart.heart_scores_antidiag(q, k, blk, stride, scores=sc, workspace=ws)
+    m1, i1, c1 = heart.heart_mask_topp(None, None, tau, scores_in=sc, n_always_kv_blocks=nt, n_dense_q_blocks=nt)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    heart.heart_mask_topp(None, None, tau, scores_in=sc, n_always_kv_blocks=nt, n_dense_q_blocks=nt,
+                          mask=m1, kept_idx=i1, kept_count=c1)
+    e1.record()
+    qblk, kblk, _, _ = heart.heart_pool_qk(q, k, blk)
+    m0, i0, c0 = heart.heart_mask_topp(qblk, kblk, tau, n_always_kv_blocks=nt, n_dense_q_blocks=nt)
+    torch.cuda.synchronize()
+    inter = (m0 & m1).sum(dim=(2, 3)).float()
+    union = (m0 | m1).sum(dim=(2, 3)).float()
+    mean_ms = sum(ms) / len(ms)
+    return {
+        "metric": "antidiagonal-style importance estimator, " + cfg.name, "data": "synthetic",
+        "stride": stride, "block": blk, "reduced_rows": M, "steps": K, "warmup": W,
+        "scores_ms": mean_ms, "scores_ms_min": ms[0],
+        "scores_tflops_bf16": flops / (mean_ms * 1e-3) / 1e12,
+        "roofline": {"kernel": "antidiag_tile_kernel + antidiag_combine_kernel", "bound": "mfma",
+                     "achieved": flops / (mean_ms * 1e-3) / 1e12, "peak": PEAK_BF16_MFMA_TFLOPS,
+                     "unit": "TFLOP/s", "frac": flops / (mean_ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS},
+        "workspace_mb": ws.numel() / 1e6,
+        "select_from_scores_us": e0.elapsed_time(e1) * 1e3,
+        "kept_block_density": {"pooled": float(m0.float().mean().item()), "antidiag": float(m1.float().mean().item())},
+        "mask_iou_with_pooled_estimator_per_head": [round(float(x), 3) for x in (inter / union).flatten().cpu().tolist()],
+    }
+
+
 def cpu_baseline(name, tau_all, delta_all):
     """Oracle timed on host cores on a bounded sample of the same workload."""
     import numpy as np
@@ -332,6 +386,9 @@ def main():
         return
     if args.ebc_demo:
         print(json.dumps(ebc_demo(args, heart, torch, g, steps_in)))
+        return
+    if args.estimator_demo:
+        print(json.dumps(estimator_demo(args, heart, torch, g, steps_in, tau)))
         return
 
     f32 = dict(dtype=torch.float32, device=dev)

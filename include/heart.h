@@ -10,8 +10,8 @@
  *   - All data pointers are DEVICE pointers owned by the caller (for instance the
  *     storage of PyTorch-ROCm tensors).  The library allocates nothing, keeps no
  *     state between calls (beyond per-device launch attributes it sets once), reads no
- *     environment variable; the one kernel that needs
- *     scratch memory takes it as a workspace argument.
+ *     environment variable; an entry point that needs scratch memory takes it as a
+ *     workspace argument.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call
  *     only enqueues kernels on that stream and returns; it never synchronises.
  *   - Return value: HEART_OK (0) or a negative error code.  After an error

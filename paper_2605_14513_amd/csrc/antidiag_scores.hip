@@ -216,64 +216,55 @@ __global__ __launch_bounds__(512, 2) void antidiag_tile_kernel(
   }
 }
 
-// One workgroup (256 lanes) per (head, query block).  Lane t owns key blocks t, t + 256, ...
+// One workgroup (4 wavefronts) per (head, query block).  A wavefront normalises two of the
+// block's 8 reduced queries on its own (global maximum over the records, normaliser, both
+// wave-wide reductions), leaves the normalised key-block masses in LDS, and after one
+// barrier the workgroup averages the 8 rows.
 __global__ __launch_bounds__(256) void antidiag_combine_kernel(int Nb, int M, int MT,
                                                               const float *__restrict__ esum,
                                                               const float *__restrict__ mref,
                                                               float *__restrict__ scores) {
-  constexpr int RQ = kAdKeysPerBlock;  // reduced queries per query block
-  constexpr int JPT = HEART_MAX_NB / 256;
-  __shared__ float s_m[RQ];
-  __shared__ float s_part[RQ][4];
+  constexpr int RQ = kAdKeysPerBlock;       // reduced queries per query block
+  constexpr int JPL = HEART_MAX_NB / 64;    // key blocks per lane
+  extern __shared__ float s_w[];            // [RQ][NbP]
   const int I = blockIdx.x % Nb;
   const long long bh = blockIdx.x / Nb;
   const int NbP = 16 * MT;
   const int a0 = I * RQ;
   const int na = min(RQ, M - a0);
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  // global maximum of each reduced query over its tile records (MT <= 64: one wavefront
-  // per pair of rows)
-  for (int rr = wave; rr < na; rr += 4) {
-    float m = lane < MT ? mref[((size_t)bh * M + a0 + rr) * MT + lane] : -__builtin_inff();
-    m = wave_max_f32(m);
-    if (lane == 0) s_m[rr] = m;
-  }
-  __syncthreads();
-  float w[RQ][JPT];
-#pragma unroll
-  for (int rr = 0; rr < RQ; ++rr) {
+  for (int rr = wave; rr < RQ; rr += 4) {
+    if (rr >= na) {  // (wave-uniform) rows past the end contribute nothing
+      for (int J = lane; J < NbP; J += 64) s_w[rr * NbP + J] = 0.f;
+      continue;
+    }
+    const size_t row = (size_t)bh * M + a0 + rr;
+    const float mr = lane < MT ? mref[row * MT + lane] : -__builtin_inff();
+    const float m = wave_max_f32(mr);
+    float w[JPL];
     float part = 0.f;
 #pragma unroll
-    for (int u = 0; u < JPT; ++u) {
-      const int J = t + 256 * u;
+    for (int u = 0; u < JPL; ++u) {
+      const int J = lane + 64 * u;
       float x = 0.f;
-      if (rr < na && J < NbP) {
-        const size_t row = (size_t)bh * M + a0 + rr;
-        x = esum[row * NbP + J] * __builtin_amdgcn_exp2f(mref[row * MT + (J >> 4)] - s_m[rr]);
-      }
-      w[rr][u] = x;
+      if (J < NbP) x = esum[row * NbP + J] * __builtin_amdgcn_exp2f(mref[row * MT + (J >> 4)] - m);
+      w[u] = x;
       part += x;
     }
-    part = wave_sum_f32(part);
-    if (lane == 0) s_part[rr][wave] = part;
+    const float inv = 1.f / wave_sum_f32(part);
+#pragma unroll
+    for (int u = 0; u < JPL; ++u) {
+      const int J = lane + 64 * u;
+      if (J < NbP) s_w[rr * NbP + J] = w[u] * inv;
+    }
   }
   __syncthreads();
-  float inv[RQ];
-#pragma unroll
-  for (int rr = 0; rr < RQ; ++rr) {
-    const float l = (s_part[rr][0] + s_part[rr][1]) + (s_part[rr][2] + s_part[rr][3]);
-    inv[rr] = rr < na ? 1.f / l : 0.f;
-  }
   const float inv_na = 1.f / (float)na;
+  for (int J = t; J < Nb; J += 256) {
+    float s = 0.f;
 #pragma unroll
-  for (int u = 0; u < JPT; ++u) {
-    const int J = t + 256 * u;
-    if (J < Nb) {
-      float s = 0.f;
-#pragma unroll
-      for (int rr = 0; rr < RQ; ++rr) s += w[rr][u] * inv[rr];
-      scores[((size_t)bh * Nb + I) * Nb + J] = s * inv_na;
-    }
+    for (int rr = 0; rr < RQ; ++rr) s += s_w[rr * NbP + J];
+    scores[((size_t)bh * Nb + I) * Nb + J] = s * inv_na;
   }
 }
 
@@ -330,7 +321,8 @@ int launch_antidiag(const heart_shape &s, const void *q, const void *k, int stri
     HEART_AD_LAUNCH(64);
 #undef HEART_AD_LAUNCH
   if (int rc = check_launch("antidiag_tile_kernel")) return rc;
-  hipLaunchKernelGGL(antidiag_combine_kernel, dim3((unsigned)((long long)BH * Nb)), dim3(256), 0, st, Nb,
+  hipLaunchKernelGGL(antidiag_combine_kernel, dim3((unsigned)((long long)BH * Nb)), dim3(256),
+                     (size_t)kAdKeysPerBlock * 16 * MT * sizeof(float), st, Nb,
                      M, MT, esum, mref, scores);
   return check_launch("antidiag_combine_kernel");
 }
