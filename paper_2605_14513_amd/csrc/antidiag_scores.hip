@@ -19,13 +19,15 @@
 //   contraction runs in stages of 64 elements (half a token row at D = 128): both operand
 //   tiles go global -> registers -> LDS (16-byte chunks XOR-swizzled by row so that the
 //   fragment reads are conflict free), double-buffered (128 KB), one barrier per stage, the
-//   loads of the next stage in flight during the MFMAs of the current one.  A wavefront owns
-//   64 reduced queries against 128 reduced keys (S^T layout: keys along the accumulator
-//   rows), so a query's maximum over those keys is a per-lane reduction plus one exchange
-//   with the partner lane.  The epilogue writes one record per (reduced query, 128 keys):
-//   the maximum m and the 16 sums over 8 keys of exp2(L - m).  Tiles are independent.
+//   loads of the next stage in flight during the MFMAs of the current one; fragments are
+//   read one contraction step ahead and the barrier sits in the shadow of the last step's
+//   MFMAs.  A wavefront owns 64 reduced queries against 128 reduced keys (S^T layout: keys
+//   along the accumulator rows), so a query's maximum over those keys is a per-lane
+//   reduction plus one exchange with the partner lane.  The epilogue writes one record per
+//   (reduced query, 128 keys): the maximum m and the 16 sums over 8 keys of exp2(L - m).
+//   Tiles are independent.
 // Kernel 2 (antidiag_combine): one workgroup per query block: global maximum and
-//   normaliser of each of its reduced queries from the tile records, then the mean over the
+//   normaliser of each of its reduced queries from the records, then the mean over the
 //   reduced queries of the rescaled key-block sums.
 #include "heart_internal.h"
 
@@ -91,26 +93,23 @@ __global__ __launch_bounds__(512, 2) void antidiag_tile_kernel(
     k_base[p] = (uint32_t)(S * (kAdTile * tk + row)) * (uint32_t)(ksn * 2) + (uint32_t)c * 16u;
     lds_w[p] = (uint32_t)(row * kAdRowB + ((c ^ ((row >> 1) & 7)) * 16));
   }
-  // two register sets: the loads of a stage are issued two stages before its MFMAs and
-  // written to LDS in the middle of the stage before (into the buffer the stage before
-  // that one has released at its closing barrier)
-  ad_u32x4 ra[2][4], rb[2][4];
-  auto load_stage = [&](int set, int st) __attribute__((always_inline)) {
+  ad_u32x4 ra[4], rb[4];
+  auto load_stage = [&](int st) __attribute__((always_inline)) {
     const int r = st / SPR, d0 = (st % SPR) * 64;
     const uint32_t qo = (uint32_t)(S - 1 - r) * (uint32_t)(qsn * 2) + (uint32_t)d0 * 2u;
     const uint32_t ko = (uint32_t)r * (uint32_t)(ksn * 2) + (uint32_t)d0 * 2u;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      ra[set][p] = __builtin_amdgcn_raw_buffer_load_b128(k_rs, k_base[p] + ko, 0, 0);
-      rb[set][p] = __builtin_amdgcn_raw_buffer_load_b128(q_rs, q_base[p] + qo, 0, 0);
+      ra[p] = __builtin_amdgcn_raw_buffer_load_b128(k_rs, k_base[p] + ko, 0, 0);
+      rb[p] = __builtin_amdgcn_raw_buffer_load_b128(q_rs, q_base[p] + qo, 0, 0);
     }
   };
-  auto store_stage = [&](int set, int buf) __attribute__((always_inline)) {
+  auto store_stage = [&](int buf) __attribute__((always_inline)) {
     unsigned char *A = smem + buf * 2 * kAdTileB, *B = A + kAdTileB;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      *reinterpret_cast<ad_u32x4 *>(A + lds_w[p]) = ra[set][p];
-      *reinterpret_cast<ad_u32x4 *>(B + lds_w[p]) = rb[set][p];
+      *reinterpret_cast<ad_u32x4 *>(A + lds_w[p]) = ra[p];
+      *reinterpret_cast<ad_u32x4 *>(B + lds_w[p]) = rb[p];
     }
   };
   // fragment of contraction step ks (16 elements) of tile row 32 x + l32: chunk 2 ks + hf
@@ -126,44 +125,61 @@ __global__ __launch_bounds__(512, 2) void antidiag_tile_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[kt][qt][r] = 0.f;
 
-  auto mfma_steps = [&](int buf, int ks0) __attribute__((always_inline)) {
+  // the six fragments of one contraction step: 4 of the keys (A operand), 2 of the queries
+  struct Frags {
+    AdFrag a[4], b[2];
+  };
+  auto read_frags = [&](Frags &f, int buf, int ks) __attribute__((always_inline)) {
     const unsigned char *A = smem + buf * 2 * kAdTileB + wi * 128 * kAdRowB;
     const unsigned char *B = smem + buf * 2 * kAdTileB + kAdTileB + wj * 64 * kAdRowB;
 #pragma unroll
-    for (int ks = ks0; ks < ks0 + 2; ++ks) {
-      AdFrag fb[2];
+    for (int qt = 0; qt < 2; ++qt)
+      f.b[qt].u = *reinterpret_cast<const ad_u32x4 *>(B + qt * 32 * kAdRowB + foff[ks]);
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+      f.a[kt].u = *reinterpret_cast<const ad_u32x4 *>(A + kt * 32 * kAdRowB + foff[ks]);
+  };
+  auto mfma8 = [&](const Frags &f) __attribute__((always_inline)) {
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
       for (int qt = 0; qt < 2; ++qt)
-        fb[qt].u = *reinterpret_cast<const ad_u32x4 *>(B + qt * 32 * kAdRowB + foff[ks]);
-#pragma unroll
-      for (int kt = 0; kt < 4; ++kt) {
-        AdFrag fa;
-        fa.u = *reinterpret_cast<const ad_u32x4 *>(A + kt * 32 * kAdRowB + foff[ks]);
-#pragma unroll
-        for (int qt = 0; qt < 2; ++qt)
-          acc[kt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, fb[qt].v, acc[kt][qt], 0, 0, 0);
-      }
-    }
+        acc[kt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[kt].v, f.b[qt].v, acc[kt][qt], 0, 0, 0);
   };
 
-  const int n_stages = S * SPR;  // even: the stride is 8 or 16
-  load_stage(0, 0);
-  load_stage(1, 1);
-  store_stage(0, 0);
+  // Per stage: the fragments of a contraction step are read one step before their MFMAs, and
+  // the barrier that hands over the next stage sits between the reads of the stage's last
+  // step and its MFMAs, so that the barrier and the first LDS reads of the next stage run in
+  // the shadow of eight MFMAs.  By the barrier a wavefront has completed all its reads of the
+  // current buffer and its writes of the next stage into the other one (released by the
+  // previous barrier).  Loads past the last stage repeat the last stage instead of being
+  // skipped, which keeps the count of outstanding loads the same on every path.
+  const int n_stages = S * SPR;
+  const int last = n_stages - 1;
+  Frags f0, f1;
+  load_stage(0);
+  store_stage(0);
   __syncthreads();
-  for (int st = 0; st < n_stages; st += 2) {
-    // stage st from buffer 0; register set 0 is free again
-    if (st + 2 < n_stages) load_stage(0, st + 2);
-    mfma_steps(0, 0);
-    store_stage(1, 1);  // stage st + 1; buffer 1 was released by the barrier before this stage
-    mfma_steps(0, 2);
+  load_stage(min(1, last));
+  read_frags(f0, 0, 0);
+  for (int st = 0; st < n_stages; ++st) {
+    const int buf = st & 1;
+    read_frags(f1, buf, 1);
+    mfma8(f0);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(f0, buf, 2);
+    mfma8(f1);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(f1, buf, 3);
+    mfma8(f0);
+    __builtin_amdgcn_sched_barrier(0);
+    store_stage(buf ^ 1);  // (after the last stage: a copy of it, never read)
     __syncthreads();
-    // stage st + 1 from buffer 1
-    if (st + 3 < n_stages) load_stage(1, st + 3);
-    mfma_steps(1, 0);
-    if (st + 2 < n_stages) store_stage(0, 0);
-    mfma_steps(1, 2);
-    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    load_stage(min(st + 2, last));
+    read_frags(f0, buf ^ 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma8(f1);
   }
 
   // ---- epilogue: record of (reduced query, 128 keys): maximum and 16 key-block sums ----------

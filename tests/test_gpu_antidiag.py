@@ -145,6 +145,22 @@ def test_full_size_sampled_heads(heart):
         assert_close(got[b, h], want, f"wan14b_480p head {h}")
 
 
+def test_largest_shape_one_head(heart):
+    """The HunyuanVideo-shaped config: 7441 reduced rows (60 records per reduced query, close to
+    the limit of 64), text tokens in front; all heads in one call, one head compared in full."""
+    g = make_generator("hunyuan_720p")
+    cfg, st = g.cfg, g.step(0)
+    print(f"antidiag largest shape N={cfg.N} H={cfg.H}", flush=True)
+    sc = heart.heart_scores_antidiag(st.q.cuda(), st.k.cuda(), cfg.block, 16)
+    torch.cuda.synchronize()
+    got = sc.cpu().numpy()
+    assert np.isfinite(got).all()
+    np.testing.assert_allclose(got.astype(np.float64).sum(axis=-1), 1.0, rtol=1e-4)
+    h = 5
+    want = oracle_scores(st.q, st.k, cfg.block, 16, {(0, h)})[(0, h)]
+    assert_close(got[0, h], want, f"hunyuan_720p head {h}")
+
+
 def test_argument_validation(heart):
     q = torch.zeros((1, 1, 256, 128), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(heart.HeartError):
