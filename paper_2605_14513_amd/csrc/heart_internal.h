@@ -81,6 +81,24 @@ __device__ __forceinline__ void swap_halves32(uint32_t v, uint32_t &r0, uint32_t
       v = OP(__builtin_bit_cast(T, r0_), __builtin_bit_cast(T, r1_));                    \
     }                                                                                    \
   } while (0)
+// The same reduction over each half (32 lanes) of the wavefront separately: the result of
+// lanes 0..31 in every lane of 0..31, that of lanes 32..63 in every lane of 32..63.
+#define HEART_HALF_REDUCE(T, v, OP)                                                      \
+  do {                                                                                   \
+    v = OP(v, __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(                          \
+                  0u, __builtin_bit_cast(uint32_t, v), 0xB1, 0xf, 0xf, false)));          \
+    v = OP(v, __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(                          \
+                  0u, __builtin_bit_cast(uint32_t, v), 0x4E, 0xf, 0xf, false)));          \
+    v = OP(v, __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(                          \
+                  0u, __builtin_bit_cast(uint32_t, v), 0x124, 0xf, 0xf, false)));         \
+    v = OP(v, __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(                          \
+                  0u, __builtin_bit_cast(uint32_t, v), 0x128, 0xf, 0xf, false)));         \
+    {                                                                                    \
+      uint32_t r0_, r1_;                                                                 \
+      swap_rows16(__builtin_bit_cast(uint32_t, v), r0_, r1_);                            \
+      v = OP(__builtin_bit_cast(T, r0_), __builtin_bit_cast(T, r1_));                    \
+    }                                                                                    \
+  } while (0)
 // (functions, not expression macros: each argument -- a DPP read -- must be evaluated
 // exactly once and with all lanes active)
 __device__ __forceinline__ uint32_t heart_op_umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
@@ -107,6 +125,22 @@ __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
   return v;
 }
 __device__ __forceinline__ int wave_sum_i32(int v) { return (int)wave_sum_u32((uint32_t)v); }
+__device__ __forceinline__ uint32_t half_sum_u32(uint32_t v) {
+  HEART_HALF_REDUCE(uint32_t, v, HEART_OP_ADD);
+  return v;
+}
+__device__ __forceinline__ uint32_t half_max_u32(uint32_t v) {
+  HEART_HALF_REDUCE(uint32_t, v, HEART_OP_UMAX);
+  return v;
+}
+__device__ __forceinline__ float half_max_f32(float v) {
+  HEART_HALF_REDUCE(float, v, HEART_OP_FMAX);
+  return v;
+}
+__device__ __forceinline__ float half_sum_f32(float v) {
+  HEART_HALF_REDUCE(float, v, HEART_OP_ADD);
+  return v;
+}
 __device__ __forceinline__ float wave_max_f32(float v) {
   HEART_WAVE_REDUCE(float, v, HEART_OP_FMAX);
   return v;

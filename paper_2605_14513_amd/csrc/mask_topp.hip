@@ -13,8 +13,10 @@
 //            global memory, no LDS staging) and converts them to fp64 on the way in.
 //            The 16 query rows sit in LDS as fp64; the key blocks of the next tile are
 //            in flight while the current tile is multiplied.
-//   Phase B  row softmax, one wavefront per row, fp32 with the accurate expf.
-//   Phase C  top-p selection, one wavefront per row, without sorting: the kept set
+//   Phase B  row softmax, fp32 with the accurate expf: one wavefront per row, or half a
+//            wavefront per row (two rows at a time) when Nb <= 256 and the scores are the
+//            kernel's own.
+//   Phase C  top-p selection, same lanes as phase B, without sorting: the kept set
 //            is "every score above a threshold value v*, plus the lowest-index
 //            ties at v*", and v* is found by a 31-step bitwise search on the fp32
 //            bit pattern (positive floats order like their bit patterns), each
@@ -113,6 +115,172 @@ __global__ __launch_bounds__(64 * kWaves) void mask_topp_kernel(
 
   const float tau_h = tau[h];
   const unsigned long long lt_mask = (1ull << lane) - 1ull;
+
+  if (!scores_in && CMAX <= 4) {
+    // ---- Phases B and C, two rows per wavefront (Nb <= 256, scores from phase A) ----------
+    // Each half of the wavefront (32 lanes) owns one row: the selection is bound by the
+    // number of vector instructions, and with 32 lanes per row every search step serves two
+    // rows and its reductions take five exchanges instead of six.  The scores of a row sum to
+    // one, so every partial sum of the fixed-point masses stays below 2^31: the mass
+    // arithmetic is 32-bit here (same integers as in the general path below, hence the same
+    // kept sets).  The per-row state (v, top, counts) is replicated over the lanes of a half.
+    constexpr int EPL = 2 * CMAX;  // elements per lane: element c is key block l32 + 32 c
+    const int l32 = lane & 31, hfw = lane >> 5;
+    const uint32_t lt32 = (1u << l32) - 1u;
+    const int r = 2 * wave + hfw;
+    const int i = i0 + r;
+    const bool row_ok = i < Nb;
+    const size_t row = (size_t)bh * Nb + (row_ok ? i : 0);
+    float p[EPL];
+    {
+      float m = -__builtin_inff();
+#pragma unroll
+      for (int c = 0; c < EPL; ++c) {
+        const int j = l32 + 32 * c;
+        p[c] = (row_ok && j < Nb) ? sP[r * NBP + j] : -__builtin_inff();
+        m = fmaxf(m, p[c]);
+      }
+      m = half_max_f32(m);
+      if (!row_ok) m = 0.f;
+      float z = 0.f;
+#pragma unroll
+      for (int c = 0; c < EPL; ++c) {
+        const int j = l32 + 32 * c;
+        p[c] = (row_ok && j < Nb) ? expf(p[c] - m) : 0.f;
+        z += p[c];
+      }
+      z = half_sum_f32(z);
+      if (!row_ok) z = 1.f;
+#pragma unroll
+      for (int c = 0; c < EPL; ++c) p[c] = __fdiv_rn(p[c], z);
+    }
+    if (scores_out && row_ok) {
+#pragma unroll
+      for (int c = 0; c < EPL; ++c) {
+        const int j = l32 + 32 * c;
+        if (j < Nb) scores_out[row * Nb + j] = p[c];
+      }
+    }
+    uint32_t e[EPL], u[EPL];
+    uint32_t my_u = 0;
+#pragma unroll
+    for (int c = 0; c < EPL; ++c) {
+      const int j = l32 + 32 * c;
+      const float pc = (j < Nb && p[c] > 0.f) ? p[c] : 0.f;
+      e[c] = __float_as_uint(pc);
+      u[c] = (uint32_t)floorf(pc * 1073741824.0f);
+      my_u += u[c];
+    }
+    const uint32_t U = half_sum_u32(my_u);
+    const bool keep_all = tau_h >= 1.0f;  // (uniform: one head per workgroup)
+    uint32_t vf = 0;
+    int cf = 0;
+    if (!keep_all) {
+      const unsigned long long T =
+          tau_h > 0.f ? (unsigned long long)floorf(tau_h * 16777216.0f) : 0ull;
+      const uint32_t need = (uint32_t)((T * (unsigned long long)U + 16777215ull) >> 24);
+      // the same bitwise search as in the general path, with the count of undecided scores
+      // kept incrementally: n_v = #(scores >= v), n_top = #(scores >= top)
+      uint32_t v = need == 0 ? 0x7fffffffu : 0u;
+      uint32_t n_v = 32 * EPL, n_top = 0;
+      bool active = need != 0;
+      for (int bit = 30; bit >= 0; --bit) {
+        if (!__any(active)) break;
+        const uint32_t cand = v | (1u << bit);
+        uint32_t s = 0, cn = 0;
+#pragma unroll
+        for (int c = 0; c < EPL; ++c) {
+          const bool ge = e[c] >= cand;
+          s += ge ? u[c] : 0u;
+          cn += ge ? 1u : 0u;
+        }
+        s = half_sum_u32(s);
+        cn = half_sum_u32(cn);
+        if (active) {
+          if (s >= need) {
+            v = cand;
+            n_v = cn;
+          } else {
+            n_top = cn;
+          }
+        }
+        const bool single = active && (n_v - n_top == 1u);
+        if (__any(single)) {
+          // the one undecided score of such a row is its threshold
+          const uint32_t top = v + (1u << bit);
+          uint32_t x = 0;
+#pragma unroll
+          for (int c = 0; c < EPL; ++c) x = (e[c] >= v && e[c] < top && e[c] > x) ? e[c] : x;
+          x = half_max_u32(x);
+          if (single) {
+            v = x > v ? x : v;
+            active = false;
+          }
+        }
+      }
+      uint32_t s_gt = 0, n_gt = 0;
+#pragma unroll
+      for (int c = 0; c < EPL; ++c) {
+        const bool gt = e[c] > v;
+        s_gt += gt ? u[c] : 0u;
+        n_gt += gt ? 1u : 0u;
+      }
+      s_gt = half_sum_u32(s_gt);
+      n_gt = half_sum_u32(n_gt);
+      uint32_t c_m = 0;
+      if (need > s_gt) {
+        const uint32_t ustar = (uint32_t)floorf(__uint_as_float(v) * 1073741824.0f);
+        c_m = (need - s_gt + ustar - 1u) / (ustar > 0u ? ustar : 1u);
+      }
+      const int k_mass = (int)(n_gt + c_m);
+      const int k_min = min(max(1, min_keep), Nb);
+      vf = v;
+      cf = (int)c_m;
+      const bool floor_wins = k_mass < k_min;
+      if (__any(floor_wins)) {
+        // the floor on the number of kept blocks: the k_min best-ranked of such a row
+        uint32_t v2 = 0;
+        for (int bit = 30; bit >= 0; --bit) {
+          const uint32_t cand = v2 | (1u << bit);
+          uint32_t cn = 0;
+#pragma unroll
+          for (int c = 0; c < EPL; ++c) cn += e[c] >= cand ? 1u : 0u;
+          cn = half_sum_u32(cn);
+          if ((int)cn >= k_min) v2 = cand;
+        }
+        uint32_t n_gt2 = 0;
+#pragma unroll
+        for (int c = 0; c < EPL; ++c) n_gt2 += (l32 + 32 * c < Nb && e[c] > v2) ? 1u : 0u;
+        n_gt2 = half_sum_u32(n_gt2);
+        if (floor_wins) {
+          vf = v2;
+          cf = k_min - (int)n_gt2;
+        }
+      }
+    }
+    const bool dense_row = i < n_dense_q;
+    int tie_run = 0, out_run = 0;
+#pragma unroll
+    for (int c = 0; c < EPL; ++c) {
+      const int j = l32 + 32 * c;
+      const bool valid = row_ok && j < Nb;
+      const bool tie = valid && e[c] == vf;
+      const unsigned long long tb = __ballot(tie);
+      const uint32_t tbh = hfw ? (uint32_t)(tb >> 32) : (uint32_t)tb;
+      const int tie_rank = tie_run + __popc(tbh & lt32);
+      tie_run += __popc(tbh);
+      const bool keep = valid && (keep_all || dense_row || j < n_always_kv || e[c] > vf ||
+                                  (tie && tie_rank < cf));
+      const unsigned long long kb = __ballot(keep);
+      const uint32_t kbh = hfw ? (uint32_t)(kb >> 32) : (uint32_t)kb;
+      const int pos = out_run + __popc(kbh & lt32);
+      out_run += __popc(kbh);
+      if (valid) mask[row * Nb + j] = keep ? 1 : 0;
+      if (keep) kept_idx[row * Nb + pos] = j;
+    }
+    if (l32 == 0 && row_ok) kept_count[row] = out_run;
+    return;
+  }
 
   for (int r = wave; r < kRows; r += kWaves) {
     const int i = i0 + r;

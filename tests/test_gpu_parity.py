@@ -233,6 +233,38 @@ def test_topp_adversarial_rows(heart, Nb):
     assert_lists_equal(gm, gi, gc, om, oi, oc, f"Nb={Nb} extras")
 
 
+@pytest.mark.parametrize("Nb", [1, 2, 31, 33, 64, 65, 100, 255, 256, 257])
+def test_topp_from_own_scores_ties_floors_and_flags(heart, Nb):
+    """The selection that follows the kernel's own score stage (two rows per wavefront up to
+    Nb = 256, one row per wavefront above): exact ties from duplicated key blocks, uniform rows
+    from identical key blocks, a threshold that truncates to zero mass, the floor on the number
+    of kept blocks, always-kept columns and dense rows, tau >= 1 -- each compared bit for bit
+    with the oracle's selection from the scores the kernel reports."""
+    B, H, D = 1, 3, 32
+    rng = np.random.default_rng(1000 + Nb)
+    qblk = (2.0 * rng.standard_normal((B, H, Nb, D))).astype(np.float32)
+    kblk = (2.0 * rng.standard_normal((B, H, Nb, D))).astype(np.float32)
+    kblk[0, 0, 1::2] = kblk[0, 0, 0:2 * (Nb // 2):2]   # head 0: key blocks in identical pairs
+    kblk[0, 1, :] = kblk[0, 1, 0]                        # head 1: all key blocks identical
+    qg, kg = np_gpu(qblk), np_gpu(kblk)
+    cases = [((0.9, 0.5, 0.95), {}), ((1e-9, 1e-9, 1e-9), {}), ((0.6, 0.6, 0.6), dict(min_keep=5)),
+             ((0.3, 0.3, 0.3), dict(min_keep=300)), ((0.8, 0.8, 0.8), dict(n_always_kv=min(2, Nb), n_dense_q=1)),
+             ((1.0, 0.7, 1.5), {})]
+    for taus, kw in cases:
+        tau = np.array(taus, np.float32)
+        sc = torch.empty((B, H, Nb, Nb), dtype=torch.float32, device="cuda")
+        gm, gi, gc = heart.heart_mask_topp(qg, kg, np_gpu(tau), scores_out=sc,
+                                           n_always_kv_blocks=kw.get("n_always_kv", 0),
+                                           n_dense_q_blocks=kw.get("n_dense_q", 0),
+                                           min_keep=kw.get("min_keep", 1))
+        torch.cuda.synchronize()
+        s = sc.cpu().numpy()
+        if Nb >= 2:
+            assert np.array_equal(s[0, 0, :, 0], s[0, 0, :, 1]), "duplicated key blocks must tie exactly"
+        om, oi, oc = oracle.topp(s, tau, **kw)
+        assert_lists_equal(gm, gi, gc, om, oi, oc, f"Nb={Nb} tau={taus} {kw}")
+
+
 def test_topp_reused_heads_are_untouched(heart):
     rng = np.random.default_rng(1)
     B, H, Nb = 2, 3, 70
