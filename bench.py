@@ -145,12 +145,17 @@ def policy_sweep(args, heart, torch, g, steps_in, tau, delta):
     # the four policies of the ablation, then the drift-threshold sweep: the paper sweeps
     # delta over {0, 10, 30, 100} with 30 its operating point; here the same ratios to the
     # synthetic operating point (delta = 0 refreshes every head whose features moved at all)
-    variants = [("always", "always", 1.0), ("heart", "heart", 1.0), ("interval:4", "interval:4", 1.0),
-                ("warmup:5", "warmup:5", 1.0), ("heart, delta x 0", "heart", 0.0),
-                ("heart, delta x 1/3", "heart", 1.0 / 3.0), ("heart, delta x 10/3", "heart", 10.0 / 3.0)]
-    for label, policy, dscale in variants:
+    variants = [("always", "always", 1.0, "pooled"), ("heart", "heart", 1.0, "pooled"),
+                ("interval:4", "interval:4", 1.0, "pooled"), ("warmup:5", "warmup:5", 1.0, "pooled"),
+                ("heart, delta x 0", "heart", 0.0, "pooled"), ("heart, delta x 1/3", "heart", 1.0 / 3.0, "pooled"),
+                ("heart, delta x 10/3", "heart", 10.0 / 3.0, "pooled"),
+                # the same with the antidiagonal-style estimator, whose cost a reused mask also saves
+                ("always, antidiag estimator", "always", 1.0, "antidiag"),
+                ("heart, antidiag estimator", "heart", 1.0, "antidiag"),
+                ("interval:4, antidiag estimator", "interval:4", 1.0, "antidiag")]
+    for label, policy, dscale, estimator in variants:
         drv = TmrDriver(TmrConfig(B=cfg.B, H=cfg.H, N=cfg.N, D=cfg.D, block=cfg.block, tau=tau,
-                                  delta=delta * dscale, policy=policy, dense_steps=5,
+                                  delta=delta * dscale, policy=policy, estimator=estimator, dense_steps=5,
                                   n_always_kv_blocks=cfg.n_text_blocks,
                                   n_dense_q_blocks=cfg.n_text_blocks),
                         n_layers=args.sweep_layers, n_branches=2, record=True, time_kernels=True)

@@ -136,15 +136,18 @@ int heart_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float 
  *   score[I,J] = mean over the reduced queries a of block I of sum_{b in block J} P[a,b]
  * (bf16 products on the matrix cores, fp32 accumulation and exponentials).  Every row of
  * `scores` sums to one up to rounding and every entry lies in [0,1].
- * q, k: bf16 with the strides of `shape` (v/o strides are ignored); scores: fp32
- * [B,H,Nb,Nb], written in full; workspace: device memory of at least
+ * q, k: bf16 with the strides of `shape` (v/o strides are ignored); refresh: uint8 [B,H]
+ * or NULL (= all heads): heads with refresh == 0 are skipped and their part of `scores`
+ * is left untouched (pass the same array to heart_mask_topp, which skips them too);
+ * scores: fp32 [B,H,Nb,Nb]; workspace: device memory of at least
  * heart_scores_antidiag_workspace_bytes(shape, stride) bytes, 16-byte aligned, contents
  * irrelevant on entry and undefined on return; calls that share a workspace must be
  * stream-ordered.  Supported: block == 8 * stride, Nb <= HEART_MAX_NB, D in {64, 128}.
  */
 size_t heart_scores_antidiag_workspace_bytes(const heart_shape *shape, int stride);
 int heart_scores_antidiag(const heart_shape *shape, const void *q, const void *k, int stride,
-                          float *scores, void *workspace, size_t workspace_bytes, void *stream);
+                          const unsigned char *refresh, float *scores, void *workspace,
+                          size_t workspace_bytes, void *stream);
 
 /*
  * Block-sparse attention consuming the mask as per-row kept-block lists

@@ -75,7 +75,7 @@ def load_library() -> ctypes.CDLL:
     lib.heart_ebc_workspace_bytes.restype = ctypes.c_size_t
     lib.heart_ebc_select.argtypes = [ci, ci, vp, vp, ctypes.c_double, vp, vp]
     lib.heart_ebc_select.restype = ci
-    lib.heart_scores_antidiag.argtypes = [sp, vp, vp, ci, vp, vp, ctypes.c_size_t, vp]
+    lib.heart_scores_antidiag.argtypes = [sp, vp, vp, ci, vp, vp, vp, ctypes.c_size_t, vp]
     lib.heart_scores_antidiag.restype = ci
     lib.heart_scores_antidiag_workspace_bytes.argtypes = [sp, ci]
     lib.heart_scores_antidiag_workspace_bytes.restype = ctypes.c_size_t
@@ -296,15 +296,18 @@ def heart_scores_antidiag_workspace_bytes(q, block: int, stride: int) -> int:
         ctypes.byref(make_shape(q, q, block)), int(stride)))
 
 
-def heart_scores_antidiag(q, k, block: int, stride: int, scores=None, workspace=None):
+def heart_scores_antidiag(q, k, block: int, stride: int, scores=None, workspace=None, refresh=None):
     """Antidiagonal-style block scores fp32 [B,H,Nb,Nb] of bf16 q, k ([B,H,N,D] views), for
     heart_mask_topp(scores_in=...).  workspace: a contiguous GPU tensor of at least
-    heart_scores_antidiag_workspace_bytes, or None (a fresh tensor from torch's allocator)."""
+    heart_scores_antidiag_workspace_bytes, or None (a fresh tensor from torch's allocator);
+    refresh: uint8 [B,H] or None: heads with 0 are skipped (their scores stay as they are)."""
     lib = load_library()
     if q.shape != k.shape:
         raise ValueError("q and k must have the same shape")
     B, H, N, D = q.shape
     Nb = (N + block - 1) // block
+    if refresh is not None and tuple(refresh.shape) != (B, H):
+        raise ValueError("refresh must be [B,H]")
     shape = make_shape(q, k, block)
     need = int(lib.heart_scores_antidiag_workspace_bytes(ctypes.byref(shape), int(stride)))
     if workspace is None:
@@ -317,6 +320,7 @@ def heart_scores_antidiag(q, k, block: int, stride: int, scores=None, workspace=
         raise ValueError("scores must be [B,H,Nb,Nb]")
     rc = lib.heart_scores_antidiag(ctypes.byref(shape), _dev(q, torch.bfloat16, "q", False),
                                    _dev(k, torch.bfloat16, "k", False), int(stride),
+                                   _dev(refresh, torch.uint8, "refresh"),
                                    _dev(scores, torch.float32, "scores"),
                                    ctypes.c_void_p(workspace.data_ptr()),
                                    workspace.numel() * workspace.element_size(), _stream())

@@ -59,7 +59,8 @@ template <int D>
 __global__ __launch_bounds__(512, 2) void antidiag_tile_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k, long long qsb, long long qsh,
     long long qsn, long long ksb, long long ksh, long long ksn, int H, int BH, int N, int S, int M,
-    int MT2, float scale_log2, float *__restrict__ esum, float *__restrict__ mref) {
+    int MT2, float scale_log2, const unsigned char *__restrict__ refresh, float *__restrict__ esum,
+    float *__restrict__ mref) {
   extern __shared__ __align__(1024) unsigned char smem[];
   // workgroup -> (head, tile): workgroup ids are dealt round-robin to the 8 XCDs; all tiles
   // of a head go to one XCD so that its operand rows are shared through that XCD's L2
@@ -67,6 +68,7 @@ __global__ __launch_bounds__(512, 2) void antidiag_tile_kernel(
   const long long slot = blockIdx.x / 8;
   const int bh = (int)(blockIdx.x % 8) + 8 * (int)(slot / tph);
   if (bh >= BH) return;
+  if (refresh && !refresh[bh]) return;  // reused head: its cached mask persists, no scores needed
   const int tile = (int)(slot % tph);
   const int tq = tile / MT2, tk = tile % MT2;
   const int b = bh / H, h = bh % H;
@@ -237,6 +239,7 @@ __global__ __launch_bounds__(512, 2) void antidiag_tile_kernel(
 // wave-wide reductions), leaves the normalised key-block masses in LDS, and after one
 // barrier the workgroup averages the 8 rows.
 __global__ __launch_bounds__(256) void antidiag_combine_kernel(int Nb, int M, int MT,
+                                                              const unsigned char *__restrict__ refresh,
                                                               const float *__restrict__ esum,
                                                               const float *__restrict__ mref,
                                                               float *__restrict__ scores) {
@@ -245,6 +248,7 @@ __global__ __launch_bounds__(256) void antidiag_combine_kernel(int Nb, int M, in
   extern __shared__ float s_w[];            // [RQ][NbP]
   const int I = blockIdx.x % Nb;
   const long long bh = blockIdx.x / Nb;
+  if (refresh && !refresh[bh]) return;
   const int NbP = 16 * MT;
   const int a0 = I * RQ;
   const int na = min(RQ, M - a0);
@@ -290,8 +294,8 @@ size_t antidiag_workspace_bytes(const heart_shape &s, int stride) {
   return (size_t)s.B * s.H * M * (16 * MT + MT) * sizeof(float);
 }
 
-int launch_antidiag(const heart_shape &s, const void *q, const void *k, int stride, float *scores,
-                    float *workspace, hipStream_t st) {
+int launch_antidiag(const heart_shape &s, const void *q, const void *k, int stride,
+                    const unsigned char *refresh, float *scores, float *workspace, hipStream_t st) {
   const int S = stride;
   const int M = (s.N + S - 1) / S;
   const int MT2 = (M + kAdTile - 1) / kAdTile;
@@ -329,7 +333,7 @@ int launch_antidiag(const heart_shape &s, const void *q, const void *k, int stri
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), kAdLds, st, (const uint16_t *)q,     \
                        (const uint16_t *)k, s.q_stride[0], s.q_stride[1], s.q_stride[2],           \
                        s.k_stride[0], s.k_stride[1], s.k_stride[2], s.H, BH, s.N, S, M, MT2,       \
-                       scale_log2, esum, mref);                                                    \
+                       scale_log2, refresh, esum, mref);                                           \
   } while (0)
   if (s.D == 128)
     HEART_AD_LAUNCH(128);
@@ -339,7 +343,7 @@ int launch_antidiag(const heart_shape &s, const void *q, const void *k, int stri
   if (int rc = check_launch("antidiag_tile_kernel")) return rc;
   hipLaunchKernelGGL(antidiag_combine_kernel, dim3((unsigned)((long long)BH * Nb)), dim3(256),
                      (size_t)kAdKeysPerBlock * 16 * MT * sizeof(float), st, Nb,
-                     M, MT, esum, mref, scores);
+                     M, MT, refresh, esum, mref, scores);
   return check_launch("antidiag_combine_kernel");
 }
 

@@ -172,7 +172,8 @@ size_t heart_scores_antidiag_workspace_bytes(const heart_shape *s, int stride) {
 }
 
 int heart_scores_antidiag(const heart_shape *shape, const void *q, const void *k, int stride,
-                          float *scores, void *workspace, size_t workspace_bytes, void *stream) {
+                          const unsigned char *refresh, float *scores, void *workspace,
+                          size_t workspace_bytes, void *stream) {
   clear_error();
   if (int rc = check_antidiag(shape, stride, "heart_scores_antidiag")) return rc;
   if (!q || !k || !scores || !workspace)
@@ -185,7 +186,8 @@ int heart_scores_antidiag(const heart_shape *shape, const void *q, const void *k
   if (workspace_bytes < heart_scores_antidiag_workspace_bytes(shape, stride))
     return fail(HEART_EINVAL, "heart_scores_antidiag: workspace of %zu bytes, need %zu", workspace_bytes,
                 heart_scores_antidiag_workspace_bytes(shape, stride));
-  return launch_antidiag(*shape, q, k, stride, scores, (float *)workspace, (hipStream_t)stream);
+  return launch_antidiag(*shape, q, k, stride, refresh, scores, (float *)workspace,
+                         (hipStream_t)stream);
 }
 
 int heart_ebc_band_error(long long C, int T, int Y, int X, const float *err, const float *dense,

@@ -173,8 +173,8 @@ int launch_attn(const heart_shape &s, const void *q, const void *k, const void *
                 const int *kept_idx, const int *kept_count, float scale, void *out, float *lse,
                 int *order, hipStream_t st);
 
-int launch_antidiag(const heart_shape &s, const void *q, const void *k, int stride, float *scores,
-                    float *workspace, hipStream_t st);
+int launch_antidiag(const heart_shape &s, const void *q, const void *k, int stride,
+                    const unsigned char *refresh, float *scores, float *workspace, hipStream_t st);
 size_t antidiag_workspace_bytes(const heart_shape &s, int stride);
 
 int launch_ebc_band_error(long long C, int T, int Y, int X, const float *err, const float *dense,

@@ -15,6 +15,11 @@ of attention layers and sequences the calls of one attention invocation:
 The first `dense_steps` denoising steps run dense attention (Experimental Setup: all
 experiments keep the first five steps dense); they neither read nor write the cache.
 
+Block importance comes from the pooled scores inside heart_mask_topp (`estimator="pooled"`) or
+from the antidiagonal-style estimator (`estimator="antidiag"`: heart_scores_antidiag, then
+heart_mask_topp on its scores); the latter is computed for refreshed heads only, so what a
+reused mask saves includes the estimator.
+
 Only call sequencing and the shared schedules live here; every array operation of the path is
 a libheart kernel.  Policies other than `heart` skip pooling on steps where nothing refreshes.
 """
@@ -40,6 +45,7 @@ class TmrConfig:
     tau: torch.Tensor            # [H] fp32 on the GPU: per-head top-p thresholds
     delta: torch.Tensor          # [H] fp32 on the GPU: drift thresholds
     policy: str = "heart"        # "heart" | "always" | "interval:<k>" | "warmup:<w>"
+    estimator: str = "pooled"    # "pooled" | "antidiag" (stride = block / 8)
     gate: Tuple[float, float] = (0.4, 0.8)
     dense_steps: int = 5
     n_always_kv_blocks: int = 0
@@ -93,6 +99,13 @@ class TmrDriver:
         self.qmean = torch.empty((B, H, D), **f32)
         self.kmean = torch.empty((B, H, D), **f32)
         self.workspace: Optional[torch.Tensor] = None
+        if cfg.estimator not in ("pooled", "antidiag"):
+            raise ValueError(f"unknown importance estimator {cfg.estimator!r}")
+        # scores and records of the antidiagonal-style estimator, shared by all layers
+        self.scores: Optional[torch.Tensor] = None
+        self.estimator_ws: Optional[torch.Tensor] = None
+        if cfg.estimator == "antidiag":
+            self.scores = torch.zeros((B, H, Nb, Nb), **f32)
         # dense lists for the warm-up steps, shared by all layers
         ar = torch.arange(Nb, dtype=torch.int32, device=self.device)
         self.dense_idx = ar.expand(B, H, Nb, Nb).contiguous()
@@ -143,7 +156,26 @@ class TmrDriver:
         if self.workspace is None:
             self.workspace = torch.empty(_b.heart_attn_workspace_bytes(q, cfg.block),
                                          dtype=torch.uint8, device=self.device)
+        if self.scores is not None and self.estimator_ws is None:
+            self.estimator_ws = torch.empty(
+                _b.heart_scores_antidiag_workspace_bytes(q, cfg.block, cfg.block // 8),
+                dtype=torch.uint8, device=self.device)
         ev: List[torch.cuda.Event] = []
+
+        def refresh_mask(refresh):
+            """Importance scores and top-p lists of the heads in `refresh` (None = all)."""
+            if self.scores is None:
+                _b.heart_mask_topp(self.qblk, self.kblk, cfg.tau, refresh=refresh,
+                                   n_always_kv_blocks=cfg.n_always_kv_blocks,
+                                   n_dense_q_blocks=cfg.n_dense_q_blocks, min_keep=cfg.min_keep,
+                                   mask=st.mask, kept_idx=st.kept_idx, kept_count=st.kept_count)
+            else:
+                _b.heart_scores_antidiag(q, k, cfg.block, cfg.block // 8, scores=self.scores,
+                                         workspace=self.estimator_ws, refresh=refresh)
+                _b.heart_mask_topp(None, None, cfg.tau, scores_in=self.scores, refresh=refresh,
+                                   n_always_kv_blocks=cfg.n_always_kv_blocks,
+                                   n_dense_q_blocks=cfg.n_dense_q_blocks, min_keep=cfg.min_keep,
+                                   mask=st.mask, kept_idx=st.kept_idx, kept_count=st.kept_count)
 
         def mark():
             if self.time_kernels:
@@ -166,21 +198,16 @@ class TmrDriver:
                 _b.heart_drift(self.qmean, self.kmean, st.qanchor, st.kanchor, st.has_anchor,
                                cfg.delta, cfg.gate[0], cfg.gate[1], True, st.drift, st.refresh)
                 mark()
-                _b.heart_mask_topp(self.qblk, self.kblk, cfg.tau, refresh=st.refresh,
-                                   n_always_kv_blocks=cfg.n_always_kv_blocks,
-                                   n_dense_q_blocks=cfg.n_dense_q_blocks, min_keep=cfg.min_keep,
-                                   mask=st.mask, kept_idx=st.kept_idx, kept_count=st.kept_count)
+                refresh_mask(st.refresh)
                 mark()
                 if self.record:
                     rec_refresh = st.refresh.clone()
             elif self._shared_schedule_refreshes(st.sparse_calls):
                 kind = "refresh"
-                _b.heart_pool_qk(q, k, cfg.block, self.qblk, self.kblk, self.qmean, self.kmean)
+                if self.scores is None:  # (the antidiagonal estimator reads q and k itself)
+                    _b.heart_pool_qk(q, k, cfg.block, self.qblk, self.kblk, self.qmean, self.kmean)
                 mark(); mark()
-                _b.heart_mask_topp(self.qblk, self.kblk, cfg.tau, refresh=None,
-                                   n_always_kv_blocks=cfg.n_always_kv_blocks,
-                                   n_dense_q_blocks=cfg.n_dense_q_blocks, min_keep=cfg.min_keep,
-                                   mask=st.mask, kept_idx=st.kept_idx, kept_count=st.kept_count)
+                refresh_mask(None)
                 mark()
             else:
                 kind = "reuse"

@@ -161,6 +161,23 @@ def test_largest_shape_one_head(heart):
     assert_close(got[0, h], want, f"hunyuan_720p head {h}")
 
 
+def test_reused_heads_are_skipped(heart):
+    """With a refresh array only the marked heads are scored; the rest of `scores` is untouched."""
+    g = make_generator("small_ragged")
+    cfg, st = g.cfg, g.step(0)
+    refresh = np.array([[1, 0, 1], [0, 0, 1]], np.uint8)
+    scores = torch.full((cfg.B, cfg.H, cfg.Nb, cfg.Nb), -7.0, device="cuda")
+    heart.heart_scores_antidiag(st.q.cuda(), st.k.cuda(), cfg.block, 16, scores=scores, refresh=np_gpu(refresh))
+    full = heart.heart_scores_antidiag(st.q.cuda(), st.k.cuda(), cfg.block, 16)
+    torch.cuda.synchronize()
+    for b in range(cfg.B):
+        for h in range(cfg.H):
+            if refresh[b, h]:
+                assert torch.equal(scores[b, h], full[b, h])
+            else:
+                assert (scores[b, h] == -7.0).all()
+
+
 def test_argument_validation(heart):
     q = torch.zeros((1, 1, 256, 128), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(heart.HeartError):
