@@ -17,9 +17,10 @@
 // Kernel 1 (antidiag_tile): one workgroup (8 wavefronts) per 256 x 256 tile of L (128 FLOP
 //   per operand byte, which keeps the operand stream from L2 below what it delivers).  The
 //   contraction runs in stages of 64 elements (half a token row at D = 128): both operand
-//   tiles go global -> registers -> LDS (16-byte chunks XOR-swizzled by row so that the
-//   fragment reads are conflict free), double-buffered (128 KB), one barrier per stage, the
-//   loads of the next stage in flight during the MFMAs of the current one; fragments are
+//   tiles go from global memory straight into LDS (`buffer_load ... lds`, 16-byte chunks
+//   XOR-swizzled by row so that the fragment reads are conflict free), double-buffered
+//   (128 KB), one barrier per stage, the loads of the next stage in flight during the MFMAs
+//   of the current one; fragments are
 //   read one contraction step ahead and the barrier sits in the shadow of the last step's
 //   MFMAs.  A wavefront owns 64 reduced queries against 128 reduced keys (S^T layout: keys
 //   along the accumulator rows), so a query's maximum over those keys is a per-lane
@@ -49,8 +50,16 @@ constexpr int kAdTileB = kAdTile * kAdRowB;      // bytes of one operand tile of
 constexpr int kAdKeysPerBlock = 8;               // reduced keys per key block (block = 8 S)
 constexpr int kAdLds = 4 * kAdTileB;             // two stages x two operands (128 KB)
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t ad_rsrc(const uint16_t *base, uint32_t bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(base), 0, (int)bytes, 0x00020000);
+// raw buffer descriptor (base, size in bytes) as four words in scalar registers, for the
+// hand-written LDS-direct loads; accesses past `bytes` return zeros
+__device__ __forceinline__ ad_u32x4 ad_rsrc_words(const uint16_t *base, uint32_t bytes) {
+  const uint64_t a = reinterpret_cast<uint64_t>(base);
+  ad_u32x4 r;
+  r.x = __builtin_amdgcn_readfirstlane((uint32_t)a);
+  r.y = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32) & 0xffffu);
+  r.z = __builtin_amdgcn_readfirstlane(bytes);
+  r.w = 0x00020000u;
+  return r;
 }
 
 }  // namespace
@@ -74,45 +83,54 @@ __global__ __launch_bounds__(512, 2) void antidiag_tile_kernel(
   const int b = bh / H, h = bh % H;
 
   const int t = threadIdx.x;
-  const int lane = t & 63, wave = t >> 6;
+  const int lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int l32 = lane & 31, hf = lane >> 5;
   const int wi = wave >> 2;  // which 128 keys of the tile
   const int wj = wave & 3;   // which 64 queries of the tile
 
-  const __amdgpu_buffer_rsrc_t q_rs = ad_rsrc(q + b * qsb + h * qsh, (uint32_t)((long long)N * qsn * 2));
-  const __amdgpu_buffer_rsrc_t k_rs = ad_rsrc(k + b * ksb + h * ksh, (uint32_t)((long long)N * ksn * 2));
+  const ad_u32x4 q_rs = ad_rsrc_words(q + b * qsb + h * qsh, (uint32_t)((long long)N * qsn * 2));
+  const ad_u32x4 k_rs = ad_rsrc_words(k + b * ksb + h * ksh, (uint32_t)((long long)N * ksn * 2));
+  const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)smem;
 
-  // staging: thread t moves chunk c = t % 8 of rows t / 8 + 64 p, p = 0..3, of both tiles.
-  // Rows of tokens >= N are out of range for the descriptor and arrive as zeros.
-  const int c = t & 7, row0 = t >> 3;
+  // Staging by LDS-direct loads: one instruction moves 16 bytes per lane to 1 KB of consecutive
+  // LDS, i.e. 8 tile rows; lane l lands at chunk position l % 8 of row l / 8 and therefore
+  // fetches the global chunk (l % 8) ^ f(row) (the XOR swizzle is applied on the global side).
+  // Wavefront w issues instructions 4 w .. 4 w + 3 of each operand tile.  The whole byte
+  // offset goes through the vector offset, which the descriptor range-checks: rows of tokens
+  // >= N are out of range and arrive as zeros.
   constexpr int SPR = D / 64;  // stages per token row
-  uint32_t q_base[4], k_base[4], lds_w[4];
+  uint32_t q_dma[4], k_dma[4];
+  {
+    const int drow = lane >> 3, dp = lane & 7;
 #pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const int row = row0 + 64 * p;
-    // (token index of sub-row 0; the stage adds its sub-row)
-    q_base[p] = (uint32_t)(S * (kAdTile * tq + row)) * (uint32_t)(qsn * 2) + (uint32_t)c * 16u;
-    k_base[p] = (uint32_t)(S * (kAdTile * tk + row)) * (uint32_t)(ksn * 2) + (uint32_t)c * 16u;
-    lds_w[p] = (uint32_t)(row * kAdRowB + ((c ^ ((row >> 1) & 7)) * 16));
+    for (int ii = 0; ii < 4; ++ii) {
+      const int row = 8 * (4 * wave + ii) + drow;
+      const uint32_t chunk = (uint32_t)(dp ^ ((row >> 1) & 7));
+      // (token index of sub-row 0; the stage adds its sub-row)
+      q_dma[ii] = (uint32_t)(S * (kAdTile * tq + row)) * (uint32_t)(qsn * 2) + chunk * 16u;
+      k_dma[ii] = (uint32_t)(S * (kAdTile * tk + row)) * (uint32_t)(ksn * 2) + chunk * 16u;
+    }
   }
-  ad_u32x4 ra[4], rb[4];
-  auto load_stage = [&](int st) __attribute__((always_inline)) {
+  // (the compiler does not see the LDS write of these instructions: their completion is
+  // awaited explicitly before the barrier that publishes the stage)
+  auto dma_stage = [&](int st, int buf) __attribute__((always_inline)) {
     const int r = st / SPR, d0 = (st % SPR) * 64;
     const uint32_t qo = (uint32_t)(S - 1 - r) * (uint32_t)(qsn * 2) + (uint32_t)d0 * 2u;
     const uint32_t ko = (uint32_t)r * (uint32_t)(ksn * 2) + (uint32_t)d0 * 2u;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      ra[p] = __builtin_amdgcn_raw_buffer_load_b128(k_rs, k_base[p] + ko, 0, 0);
-      rb[p] = __builtin_amdgcn_raw_buffer_load_b128(q_rs, q_base[p] + qo, 0, 0);
+    for (int ii = 0; ii < 4; ++ii) {
+      const uint32_t dst_a = smem_lds + (uint32_t)(buf * 2 * kAdTileB + (4 * wave + ii) * 1024);
+      const uint32_t dst_b = dst_a + (uint32_t)kAdTileB;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                   :: "s"(dst_a), "v"(k_dma[ii] + ko), "s"(k_rs) : "memory");
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                   :: "s"(dst_b), "v"(q_dma[ii] + qo), "s"(q_rs) : "memory");
     }
   };
-  auto store_stage = [&](int buf) __attribute__((always_inline)) {
-    unsigned char *A = smem + buf * 2 * kAdTileB, *B = A + kAdTileB;
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      *reinterpret_cast<ad_u32x4 *>(A + lds_w[p]) = ra[p];
-      *reinterpret_cast<ad_u32x4 *>(B + lds_w[p]) = rb[p];
-    }
+  auto wait_loads_and_barrier = [&]() __attribute__((always_inline)) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
   };
   // fragment of contraction step ks (16 elements) of tile row 32 x + l32: chunk 2 ks + hf
   uint32_t foff[4];
@@ -153,16 +171,15 @@ __global__ __launch_bounds__(512, 2) void antidiag_tile_kernel(
   // the barrier that hands over the next stage sits between the reads of the stage's last
   // step and its MFMAs, so that the barrier and the first LDS reads of the next stage run in
   // the shadow of eight MFMAs.  By the barrier a wavefront has completed all its reads of the
-  // current buffer and its writes of the next stage into the other one (released by the
-  // previous barrier).  Loads past the last stage repeat the last stage instead of being
-  // skipped, which keeps the count of outstanding loads the same on every path.
+  // current buffer and its loads of the next stage into the other one; right after it, it
+  // issues the loads of the stage after that into the buffer just released.  Loads past the
+  // last stage repeat the last stage (into a buffer nobody reads any more).
   const int n_stages = S * SPR;
   const int last = n_stages - 1;
   Frags f0, f1;
-  load_stage(0);
-  store_stage(0);
-  __syncthreads();
-  load_stage(min(1, last));
+  dma_stage(0, 0);
+  wait_loads_and_barrier();
+  dma_stage(min(1, last), 1);
   read_frags(f0, 0, 0);
   for (int st = 0; st < n_stages; ++st) {
     const int buf = st & 1;
@@ -175,14 +192,15 @@ __global__ __launch_bounds__(512, 2) void antidiag_tile_kernel(
     read_frags(f1, buf, 3);
     mfma8(f0);
     __builtin_amdgcn_sched_barrier(0);
-    store_stage(buf ^ 1);  // (after the last stage: a copy of it, never read)
-    __syncthreads();
+    wait_loads_and_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    load_stage(min(st + 2, last));
+    dma_stage(min(st + 2, last), buf);
     read_frags(f0, buf ^ 1, 0);
     __builtin_amdgcn_sched_barrier(0);
     mfma8(f1);
   }
+  // loads of the repeated last stage may still be in flight towards LDS
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   // ---- epilogue: record of (reduced query, 128 keys): maximum and 16 key-block sums ----------
   // accumulator element r of key tile kt: reduced key key0 + 32 kt + 8 (r / 4) + 4 hf + r % 4
