@@ -254,15 +254,16 @@ __global__ __launch_bounds__(512, 2) void antidiag_tile_kernel(
 
 // One workgroup (4 wavefronts) per (head, query block).  A wavefront normalises two of the
 // block's 8 reduced queries on its own (global maximum over the records, normaliser, both
-// wave-wide reductions), leaves the normalised key-block masses in LDS, and after one
-// barrier the workgroup averages the 8 rows.
+// wave-wide reductions; the loads of both rows are issued before either is reduced), leaves
+// the normalised key-block masses in LDS, and after one barrier the workgroup averages the
+// 8 rows.  JPL = key blocks per lane (16 MT <= 64 JPL).
+template <int JPL>
 __global__ __launch_bounds__(256) void antidiag_combine_kernel(int Nb, int M, int MT,
                                                               const unsigned char *__restrict__ refresh,
                                                               const float *__restrict__ esum,
                                                               const float *__restrict__ mref,
                                                               float *__restrict__ scores) {
   constexpr int RQ = kAdKeysPerBlock;       // reduced queries per query block
-  constexpr int JPL = HEART_MAX_NB / 64;    // key blocks per lane
   extern __shared__ float s_w[];            // [RQ][NbP]
   const int I = blockIdx.x % Nb;
   const long long bh = blockIdx.x / Nb;
@@ -271,29 +272,35 @@ __global__ __launch_bounds__(256) void antidiag_combine_kernel(int Nb, int M, in
   const int a0 = I * RQ;
   const int na = min(RQ, M - a0);
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  for (int rr = wave; rr < RQ; rr += 4) {
-    if (rr >= na) {  // (wave-uniform) rows past the end contribute nothing
-      for (int J = lane; J < NbP; J += 64) s_w[rr * NbP + J] = 0.f;
-      continue;
+  float mr[2], w[2][JPL], mj[2][JPL];
+#pragma unroll
+  for (int x = 0; x < 2; ++x) {
+    const int rr = wave + 4 * x;
+    const size_t row = (size_t)bh * M + a0 + (rr < na ? rr : 0);  // (rows past the end: loads of row 0, unused)
+    mr[x] = lane < MT ? mref[row * MT + lane] : -__builtin_inff();
+#pragma unroll
+    for (int u = 0; u < JPL; ++u) {
+      const int J = lane + 64 * u;
+      w[x][u] = J < NbP ? esum[row * NbP + J] : 0.f;
+      mj[x][u] = J < NbP ? mref[row * MT + (J >> 4)] : 0.f;
     }
-    const size_t row = (size_t)bh * M + a0 + rr;
-    const float mr = lane < MT ? mref[row * MT + lane] : -__builtin_inff();
-    const float m = wave_max_f32(mr);
-    float w[JPL];
+  }
+#pragma unroll
+  for (int x = 0; x < 2; ++x) {
+    const int rr = wave + 4 * x;
+    const float m = wave_max_f32(mr[x]);
     float part = 0.f;
 #pragma unroll
     for (int u = 0; u < JPL; ++u) {
       const int J = lane + 64 * u;
-      float x = 0.f;
-      if (J < NbP) x = esum[row * NbP + J] * __builtin_amdgcn_exp2f(mref[row * MT + (J >> 4)] - m);
-      w[u] = x;
-      part += x;
+      w[x][u] = J < NbP ? w[x][u] * __builtin_amdgcn_exp2f(mj[x][u] - m) : 0.f;
+      part += w[x][u];
     }
-    const float inv = 1.f / wave_sum_f32(part);
+    const float inv = rr < na ? 1.f / wave_sum_f32(part) : 0.f;
 #pragma unroll
     for (int u = 0; u < JPL; ++u) {
       const int J = lane + 64 * u;
-      if (J < NbP) s_w[rr * NbP + J] = w[u] * inv;
+      if (J < NbP) s_w[rr * NbP + J] = w[x][u] * inv;
     }
   }
   __syncthreads();
@@ -359,9 +366,17 @@ int launch_antidiag(const heart_shape &s, const void *q, const void *k, int stri
     HEART_AD_LAUNCH(64);
 #undef HEART_AD_LAUNCH
   if (int rc = check_launch("antidiag_tile_kernel")) return rc;
-  hipLaunchKernelGGL(antidiag_combine_kernel, dim3((unsigned)((long long)BH * Nb)), dim3(256),
-                     (size_t)kAdKeysPerBlock * 16 * MT * sizeof(float), st, Nb,
-                     M, MT, refresh, esum, mref, scores);
+  const dim3 cgrid((unsigned)((long long)BH * Nb));
+  const size_t clds = (size_t)kAdKeysPerBlock * 16 * MT * sizeof(float);
+  if (MT <= 16)
+    hipLaunchKernelGGL(antidiag_combine_kernel<4>, cgrid, dim3(256), clds, st, Nb, M, MT, refresh, esum,
+                       mref, scores);
+  else if (MT <= 32)
+    hipLaunchKernelGGL(antidiag_combine_kernel<8>, cgrid, dim3(256), clds, st, Nb, M, MT, refresh, esum,
+                       mref, scores);
+  else
+    hipLaunchKernelGGL(antidiag_combine_kernel<16>, cgrid, dim3(256), clds, st, Nb, M, MT, refresh, esum,
+                       mref, scores);
   return check_launch("antidiag_combine_kernel");
 }
 
