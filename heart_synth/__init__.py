@@ -86,28 +86,28 @@ class HeartConfig:
 
 
 CONFIGS: Dict[str, HeartConfig] = {
-    # BASELINE configs[0]
+    # the five benchmark configurations, smallest first: (1) tiny
     "tiny": HeartConfig(
         name="tiny", B=1, H=2, D=64, grid=(4, 16, 16), block=64, seed=0, steps=2,
         gain=6.0, tau_spec=("list", (0.9, 0.95)), delta=0.05, schedule="tiny",
         locality=(1.0, 1.0),
     ),
-    # BASELINE configs[1]
+    # (2) Wan2.1-1.3B at 480P
     "wan1p3b_480p": HeartConfig(
         name="wan1p3b_480p", B=1, H=12, D=128, grid=(21, 30, 52), block=128, seed=1,
         steps=2, tau_spec=("uniform", 0.85, 0.98), delta=0.01, schedule="loguniform",
     ),
-    # BASELINE configs[2] (headline)
+    # (3) Wan2.1-14B at 480P: the shape the headline metric is quoted on
     "wan14b_480p": HeartConfig(
         name="wan14b_480p", B=1, H=40, D=128, grid=(21, 30, 52), block=128, seed=2,
         steps=10, tau_spec=("uniform", 0.85, 0.98), delta=1.0, schedule="jumps",
     ),
-    # BASELINE configs[3]
+    # (4) Wan2.1-14B at 720P
     "wan14b_720p": HeartConfig(
         name="wan14b_720p", B=1, H=40, D=128, grid=(21, 45, 80), block=128, seed=3,
         steps=2, tau_spec=("uniform", 0.85, 0.98), delta=1.0, schedule="jumps",
     ),
-    # BASELINE configs[4]
+    # (5) HunyuanVideo-shaped, 720P, with text tokens in front
     "hunyuan_720p": HeartConfig(
         name="hunyuan_720p", B=1, H=24, D=128, grid=(33, 45, 80), block=128, seed=4,
         n_text=256, steps=10, tau_spec=("uniform", 0.80, 0.98), delta=1.0,
@@ -204,7 +204,7 @@ class HeartInputGenerator:
         inc = np.zeros((S, H), dtype=np.float64)
         noise = np.zeros((S, H), dtype=np.float64)  # std of iid noise at step s vs step 0
         if cfg.schedule == "tiny":
-            # BASELINE configs[0]: step 2 = step 1 + N(0, 0.02) on head 0, N(0, 0.5) on head 1
+            # tiny configuration: step 2 = step 1 + N(0, 0.02) on head 0, N(0, 0.5) on head 1
             sig = [0.02, 0.5]
             for s in range(1, S):
                 for h in range(H):

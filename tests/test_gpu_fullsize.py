@@ -1,4 +1,4 @@
-"""Parity at the full sizes of the BASELINE configurations, in the launch configuration
+"""Parity at the full sizes of the benchmark configurations, in the launch configuration
 bench.py times (all heads of the workload in one call).
 
 The oracle is cheap for pooling, drift, scores and top-p even at these sizes, so those
@@ -32,7 +32,7 @@ def heart():
 
 def density_tau(scores, target, nt):
     """Per-head tau by bisection (CPU, oracle top-p) so that each head keeps about
-    `target` of its blocks -- BASELINE config 4 asks for a global density of 15 %."""
+    `target` of its blocks -- the 720P Wan-14B configuration asks for a global density of 15 %."""
     B, H, Nb, _ = scores.shape
     lo = np.full(H, 0.05, np.float32)
     hi = np.full(H, 0.9999, np.float32)
