@@ -15,7 +15,8 @@ from heart_testlib import gpu, np_gpu
 pytestmark = pytest.mark.gpu
 
 
-def test_captured_step_replays_bit_exact():
+@pytest.mark.parametrize("estimator", ["pooled", "antidiag"])
+def test_captured_step_replays_bit_exact(estimator):
     import paper_2605_14513_amd as heart
 
     g = make_generator("small_text")
@@ -41,14 +42,25 @@ def test_captured_step_replays_bit_exact():
             kcnt=torch.zeros((B, H, Nb), dtype=torch.int32, device=dev),
             out=torch.zeros((B, H, N, D), dtype=torch.bfloat16, device=dev),
             ws=torch.empty(heart.heart_attn_workspace_bytes(
-                torch.empty((B, H, N, D), dtype=torch.bfloat16, device=dev), blk), dtype=torch.uint8, device=dev))
+                torch.empty((B, H, N, D), dtype=torch.bfloat16, device=dev), blk), dtype=torch.uint8, device=dev),
+            scores=torch.zeros((B, H, Nb, Nb), **f32),
+            ews=torch.empty(heart.heart_scores_antidiag_workspace_bytes(
+                torch.empty((B, H, N, D), dtype=torch.bfloat16, device=dev), blk, blk // 8),
+                dtype=torch.uint8, device=dev))
 
     def step(s):
         heart.heart_pool_qk(s["q"], s["k"], blk, s["qblk"], s["kblk"], s["qmean"], s["kmean"])
         heart.heart_drift(s["qmean"], s["kmean"], s["qa"], s["ka"], s["has"], delta, 0.4, 0.8, True,
                           s["drift"], s["refresh"])
-        heart.heart_mask_topp(s["qblk"], s["kblk"], tau, refresh=s["refresh"], n_always_kv_blocks=nt,
-                              n_dense_q_blocks=nt, mask=s["mask"], kept_idx=s["kidx"], kept_count=s["kcnt"])
+        if estimator == "pooled":
+            heart.heart_mask_topp(s["qblk"], s["kblk"], tau, refresh=s["refresh"], n_always_kv_blocks=nt,
+                                  n_dense_q_blocks=nt, mask=s["mask"], kept_idx=s["kidx"], kept_count=s["kcnt"])
+        else:
+            heart.heart_scores_antidiag(s["q"], s["k"], blk, blk // 8, scores=s["scores"], workspace=s["ews"],
+                                        refresh=s["refresh"])
+            heart.heart_mask_topp(None, None, tau, scores_in=s["scores"], refresh=s["refresh"],
+                                  n_always_kv_blocks=nt, n_dense_q_blocks=nt, mask=s["mask"],
+                                  kept_idx=s["kidx"], kept_count=s["kcnt"])
         heart.heart_block_sparse_attn(s["q"], s["k"], s["v"], blk, s["kidx"], s["kcnt"], out=s["out"],
                                       workspace=s["ws"])
 
@@ -74,7 +86,7 @@ def test_captured_step_replays_bit_exact():
         step(cap)
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
-    for key in ("qa", "ka", "has", "mask", "kidx", "kcnt", "out"):
+    for key in ("qa", "ka", "has", "mask", "kidx", "kcnt", "out", "scores"):
         cap[key].zero_()
     graph = torch.cuda.CUDAGraph()
     load(cap, steps[0])
