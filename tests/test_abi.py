@@ -82,6 +82,36 @@ def test_host_validation_rejects_bad_calls_without_a_gpu(lib):
                                None, None, None) == -1
 
 
+def test_estimator_validation_without_a_gpu(lib):
+    """heart_scores_antidiag checks shape, stride relation, pointers, alignment and workspace
+    size on the host; the pointers below are never dereferenced."""
+    from paper_2605_14513_amd.binding import HeartShape
+
+    s = HeartShape()
+    s.B, s.H, s.N, s.D, s.block = 1, 2, 1000, 128, 128
+    for arr in (s.q_stride, s.k_stride, s.v_stride, s.o_stride):
+        arr[0], arr[1], arr[2] = 2 * 1000 * 128, 1000 * 128, 128
+    fake = ctypes.c_void_p(0x10000)
+    call = lib.heart_scores_antidiag
+    assert call(None, fake, fake, 16, None, fake, fake, 1 << 30, None) == -1
+    assert call(ctypes.byref(s), fake, fake, 8, None, fake, fake, 1 << 30, None) == -2
+    assert b"8 * stride" in lib.heart_last_error()
+    assert call(ctypes.byref(s), None, fake, 16, None, fake, fake, 1 << 30, None) == -1
+    assert call(ctypes.byref(s), ctypes.c_void_p(0x10008), fake, 16, None, fake, fake, 1 << 30, None) == -2
+    need = lib.heart_scores_antidiag_workspace_bytes(ctypes.byref(s), 16)
+    # 63 reduced rows -> one 256-row tile -> 2 records of 128 keys: 16 * 2 sums + 2 maxima per row
+    assert need == 1 * 2 * 63 * (32 + 2) * 4
+    assert call(ctypes.byref(s), fake, fake, 16, None, fake, fake, need - 1, None) == -1
+    assert b"workspace" in lib.heart_last_error()
+    s.k_stride[2] = 132   # not a multiple of 8 elements
+    assert call(ctypes.byref(s), fake, fake, 16, None, fake, fake, need, None) == -2
+    s.k_stride[2] = 128
+    s.N = 128 * 1025      # more key blocks than the mask kernel ranks
+    assert call(ctypes.byref(s), fake, fake, 16, None, fake, fake, 1 << 40, None) == -2
+    assert b"HEART_MAX_NB" in lib.heart_last_error()
+    assert lib.heart_scores_antidiag_workspace_bytes(None, 16) == 0
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
 
