@@ -440,6 +440,52 @@ def test_tiny_config_end_to_end_sanity():
         assert r[0].tolist() == want, (delta, d)
 
 
+def test_pooled_drift_against_the_full_token_drift_of_the_appendix():
+    """App. query-key stability: the full-token drift d (mean over tokens of the L1 change of q
+    plus that of k) bounds the mean change of the scaled logits by max(B_q, B_k) / sqrt(D) * d
+    (Hoelder), and the online proxy (L1 distance of the token means) can only be smaller than d
+    (triangle inequality) -- with equality when every token moves by the same vector.  Pins
+    pool + drift together against quantities computed token by token in numpy."""
+    rng = np.random.default_rng(5)
+    N, D, blk = 300, 64, 64
+    qa = bf16_vals(bf16_bits(rng.standard_normal((1, 1, N, D))))
+    ka = bf16_vals(bf16_bits(rng.standard_normal((1, 1, N, D))))
+    qb = bf16_vals(bf16_bits(qa + 0.25 * rng.standard_normal((1, 1, N, D))))
+    kb = bf16_vals(bf16_bits(ka + 0.25 * rng.standard_normal((1, 1, N, D))))
+
+    def proxy(q0, k0, q1, k1):
+        _, qm0 = oracle.pool(bf16_bits(q0), blk)
+        _, km0 = oracle.pool(bf16_bits(k0), blk)
+        _, qm1 = oracle.pool(bf16_bits(q1), blk)
+        _, km1 = oracle.pool(bf16_bits(k1), blk)
+        has = np.ones((1, 1), np.uint8)
+        d, _ = oracle.drift(qm1, km1, qm0.copy(), km0.copy(), has, np.zeros(1, np.float32), 0.0, 1.0,
+                            commit=False)
+        return float(d[0, 0])
+
+    dq, dk = qb - qa, kb - ka
+    full = np.abs(dq[0, 0]).sum(axis=1).mean() + np.abs(dk[0, 0]).sum(axis=1).mean()
+    d_proxy = proxy(qa, ka, qb, kb)
+    assert 0.0 < d_proxy <= full * (1 + 1e-6)
+    assert d_proxy < 0.5 * full          # iid changes average out in the token mean
+    # the Hoelder bound on the mean logit change (ties the full-token drift to what it is for)
+    ga = qa[0, 0] @ ka[0, 0].T / np.sqrt(D)
+    gb = qb[0, 0] @ kb[0, 0].T / np.sqrt(D)
+    bq = max(np.abs(qa).max(), np.abs(qb).max())
+    bk = max(np.abs(ka).max(), np.abs(kb).max())
+    assert np.abs(gb - ga).mean() <= max(bq, bk) / np.sqrt(D) * full
+    # a common offset: proxy == full-token drift (values chosen exactly representable in bf16)
+    cq = np.zeros(D); cq[::2] = 0.5; cq[1::4] = -0.25
+    ck = np.zeros(D); ck[::3] = 1.0
+    q0 = np.round(qa * 8) / 8
+    k0 = np.round(ka * 8) / 8
+    q1, k1 = q0 + cq, k0 + ck
+    full_c = np.abs(cq).sum() + np.abs(ck).sum()
+    assert abs(proxy(q0, k0, q1, k1) - full_c) <= 1e-5 * full_c
+    # and it is the SUM of the two terms: moving only the keys gives only the key term
+    assert abs(proxy(q0, k0, q0, k1) - np.abs(ck).sum()) <= 1e-5 * full_c
+
+
 def test_drift_and_mask_stability_are_negatively_related():
     """Sec. 4.1 / 4.2 (the observation TMR rests on): heads whose pooled Q/K features have drifted
     more from the anchor step have masks that overlap less with the anchor mask.  Sign only:
