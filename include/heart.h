@@ -157,6 +157,11 @@ int heart_scores_antidiag(const heart_shape *shape, const void *q, const void *k
  *     out[n,:] = sum_t softmax_t( q_n . k_t * scale ) v_t,   t over the real tokens of
  *     the key blocks kept_idx[b,h,i,0..kept_count[b,h,i])
  *   computed flash-style (online softmax) with bf16 MFMA and fp32 accumulation.
+ *   Precision: q is multiplied by scale * log2(e) and rounded to bf16 once (the error of one
+ *   more bf16 rounding of the query), the softmax weights are rounded to bf16 for the second
+ *   contraction, everything else is fp32.  For q, k, v of unit scale (logits of a few units)
+ *   the output is within 2e-2 of exact attention on the given bf16 inputs; the error grows
+ *   with the cube of the input scale.
  * q, k, v: bf16 with the strides of `shape`; out: bf16 with o_stride; kept_idx /
  * kept_count as written by heart_mask_topp (indices must lie in [0, Nb); order
  * does not matter for the result up to rounding); scale <= 0 means 1/sqrt(D);

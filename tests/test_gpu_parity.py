@@ -448,6 +448,28 @@ def test_chained_steps_match_oracle(heart, name):
 
 
 # ------------------------------------------------------------------------------ shapes
+@pytest.mark.parametrize("amp", [0.5, 1.0, 2.0])
+def test_attn_error_against_input_magnitude(heart, amp):
+    """Precision contract of the attention kernel: Q is multiplied by scale * log2(e) and rounded
+    to bf16 once, i.e. every logit carries the error of one more bf16 rounding of the query
+    (relative 2^-9 per element).  On iid N(0, amp^2) inputs the logits have standard deviation
+    amp^2 and the values amp, so the output error grows like amp^3: inside the 2e-2 budget at
+    amp <= 1 (logits of a few units, what normalised q and k give), about 8 x that at amp = 2
+    (logits of +-12, nearly one-hot rows)."""
+    B, H, N, D, blk = 1, 2, 700, 128, 128
+    Nb = (N + blk - 1) // blk
+    gen = torch.Generator().manual_seed(int(amp * 10))
+    q, k, v = ((amp * torch.randn((B, H, N, D), generator=gen)).bfloat16() for _ in range(3))
+    idx = np.broadcast_to(np.arange(Nb, dtype=np.int32), (B, H, Nb, Nb)).copy()
+    cnt = np.full((B, H, Nb), Nb, np.int32)
+    out = heart.heart_block_sparse_attn(gpu(q), gpu(k), gpu(v), blk, np_gpu(idx), np_gpu(cnt))
+    torch.cuda.synchronize()
+    want = oracle.attn(u16(q), u16(k), u16(v), blk, idx, cnt)
+    err = np.abs(out.float().cpu().numpy().astype(np.float64) - want).max()
+    print(f"amp {amp}: max abs err {err:.4f} (outputs up to {np.abs(want).max():.1f})", flush=True)
+    assert err <= ATTN_ATOL * max(1.0, amp ** 3)
+
+
 @pytest.mark.parametrize("B,H,N,D,blk", [
     (1, 1, 33, 128, 128),     # one ragged block, a single head: 7 of the 8 XCD lists are empty
     (1, 1, 100, 64, 64),      # two blocks, the second ragged
