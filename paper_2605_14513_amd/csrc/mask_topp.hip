@@ -13,9 +13,9 @@
 //            global memory, no LDS staging) and converts them to fp64 on the way in.
 //            The 16 query rows sit in LDS as fp64; the key blocks of the next tile are
 //            in flight while the current tile is multiplied.
-//   Phase B  row softmax, fp32 with the accurate expf: one wavefront per row, or half a
-//            wavefront per row (two rows at a time) when Nb <= 256 and the scores are the
-//            kernel's own.
+//   Phase B  row softmax, fp32 with the accurate expf: half a wavefront per row (two rows at
+//            a time) when the scores are the kernel's own, one wavefront per row for scores
+//            passed in.
 //   Phase C  top-p selection, same lanes as phase B, without sorting: the kept set
 //            is "every score above a threshold value v*, plus the lowest-index
 //            ties at v*", and v* is found by a 31-step bitwise search on the fp32
@@ -116,8 +116,8 @@ __global__ __launch_bounds__(64 * kWaves) void mask_topp_kernel(
   const float tau_h = tau[h];
   const unsigned long long lt_mask = (1ull << lane) - 1ull;
 
-  if (!scores_in && CMAX <= 4) {
-    // ---- Phases B and C, two rows per wavefront (Nb <= 256, scores from phase A) ----------
+  if (!scores_in) {
+    // ---- Phases B and C, two rows per wavefront (scores from phase A) ----------------------
     // Each half of the wavefront (32 lanes) owns one row: the selection is bound by the
     // number of vector instructions, and with 32 lanes per row every search step serves two
     // rows and its reductions take five exchanges instead of six.  The scores of a row sum to

@@ -233,10 +233,10 @@ def test_topp_adversarial_rows(heart, Nb):
     assert_lists_equal(gm, gi, gc, om, oi, oc, f"Nb={Nb} extras")
 
 
-@pytest.mark.parametrize("Nb", [1, 2, 31, 33, 64, 65, 100, 255, 256, 257])
+@pytest.mark.parametrize("Nb", [1, 2, 31, 33, 64, 65, 100, 255, 256, 257, 511, 600, 931, 1024])
 def test_topp_from_own_scores_ties_floors_and_flags(heart, Nb):
-    """The selection that follows the kernel's own score stage (two rows per wavefront up to
-    Nb = 256, one row per wavefront above): exact ties from duplicated key blocks, uniform rows
+    """The selection that follows the kernel's own score stage (two rows per wavefront, at every
+    lane-slot width): exact ties from duplicated key blocks, uniform rows
     from identical key blocks, a threshold that truncates to zero mass, the floor on the number
     of kept blocks, always-kept columns and dense rows, tau >= 1 -- each compared bit for bit
     with the oracle's selection from the scores the kernel reports."""
