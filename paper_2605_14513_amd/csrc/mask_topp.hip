@@ -467,9 +467,14 @@ int launch_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float
 #define HEART_TOPP_ARGS                                                                       \
   B, H, Nb, D, qblk, kblk, scores_in, tau, refresh, n_always_kv, n_dense_q, min_keep, mask,   \
       kept_idx, kept_count, scores_out, st
+  // (lane slots in steps of 128 key blocks above 256: unused slots cost selection work)
   if (Nb <= 64) return launch_cmax<1>(HEART_TOPP_ARGS);
   if (Nb <= 256) return launch_cmax<4>(HEART_TOPP_ARGS);
+  if (Nb <= 384) return launch_cmax<6>(HEART_TOPP_ARGS);
   if (Nb <= 512) return launch_cmax<8>(HEART_TOPP_ARGS);
+  if (Nb <= 640) return launch_cmax<10>(HEART_TOPP_ARGS);
+  if (Nb <= 768) return launch_cmax<12>(HEART_TOPP_ARGS);
+  if (Nb <= 896) return launch_cmax<14>(HEART_TOPP_ARGS);
   return launch_cmax<16>(HEART_TOPP_ARGS);
 #undef HEART_TOPP_ARGS
 }
