@@ -241,6 +241,13 @@ __global__ __launch_bounds__(256) void attn_order_kernel(const int *__restrict__
   }
 }
 
+// 1: keep Q as it is and scale every logit in fp32 (one more multiply per logit, 3-4 % slower);
+// the error then stays at the bf16 rounding of the weights and of the output for any input
+// scale.  0: fold the softmax scale into Q once (one more bf16 rounding of the query; the
+// error grows with the cube of the input scale, inside the budget for inputs of unit scale).
+#ifndef HEART_ATTN_EXACT_SCALE
+#define HEART_ATTN_EXACT_SCALE 0
+#endif
 #ifndef HEART_ATTN_PF
 #define HEART_ATTN_PF 4  // LDS fragment reads in flight ahead of the MFMAs
 #endif
@@ -268,7 +275,15 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   constexpr int IPW = kStageRows / RPI / NW;  // such instructions per wavefront and tile
   constexpr int NSL = BLK / 32;          // 32-key slices per key block
   constexpr int SO = D + 8;              // LDS row stride of the output staging (elements)
+#if HEART_ATTN_EXACT_SCALE
+  // (accumulators, maxima and the reference exponent are in raw logit units; kLogitScale
+  // takes them to log2 units where they enter an exponential)
+  const float kLogitScale = scale_log2e;
+  const float kRescaleSlack = 8.f / scale_log2e;
+#else
+  constexpr float kLogitScale = 1.f;     // the accumulators already are in log2 units
   constexpr float kRescaleSlack = 8.f;   // log2 units the running reference may lag the max
+#endif
   static_assert(NW % 2 == 0 && IPW >= 1 && (NSL == 2 || NSL == 4), "tile layout");
 
   // LDS: [K stage 0][K stage 1][V stage 0][V stage 1], reused for the output at the end
@@ -369,6 +384,7 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
       qf[ks].u = __builtin_amdgcn_raw_buffer_load_b128(q_rs, q_off + ks * 32, 0, 0);
+#if !HEART_ATTN_EXACT_SCALE
     // fold the softmax scale and log2(e) into Q once: S^T then comes out of the matrix
     // cores in log2 units and no per-logit multiply is left on the VALU
 #pragma unroll
@@ -376,6 +392,7 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
 #pragma unroll
       for (int w = 0; w < 4; ++w)
         qf[ks].u[w] = cvt_pk_bf16(bf16lo(qf[ks].u[w]) * scale_log2e, bf16hi(qf[ks].u[w]) * scale_log2e);
+#endif
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -470,10 +487,10 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
     // (the empty asm statements pin each result to its slot: without them the compiler
     // sinks the whole computation to its first use, out of the MFMA shadow)
     if (st == 0) {
-      xt0 = __builtin_amdgcn_exp2f(x[r]);
+      xt0 = __builtin_amdgcn_exp2f(x[r] * kLogitScale);
       asm volatile("" : "+v"(xt0));
     } else if (st == 1) {
-      xt1 = __builtin_amdgcn_exp2f(x[r + 1]);
+      xt1 = __builtin_amdgcn_exp2f(x[r + 1] * kLogitScale);
       asm volatile("" : "+v"(xt1));
     } else {
       // (plain adds for the row sum: they co-issue with MFMAs, dot instructions do not)
@@ -534,7 +551,7 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
       const float base = first ? 0.f : m_ref;       // what the accumulators are relative to
       const float delta = bump ? m_rel : 0.f;
       const float m_new = bump ? base + m_rel : m_ref;
-      const float alpha = bump ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.f;  // 0 the first time
+      const float alpha = bump ? __builtin_amdgcn_exp2f((m_ref - m_new) * kLogitScale) : 1.f;  // 0 the first time
       l_run *= alpha;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
@@ -750,7 +767,7 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   if (lse && hf == 0 && qrow < N)
     lse[(size_t)bh * N + qrow] =
-        l_tot > 0.f ? (m_ref + log2f(l_tot)) * 0.6931471805599453f : -__builtin_inff();
+        l_tot > 0.f ? (m_ref * kLogitScale + log2f(l_tot)) * 0.6931471805599453f : -__builtin_inff();
   uint16_t *sO = reinterpret_cast<uint16_t *>(smem);  // [BLK][SO]
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
