@@ -88,7 +88,7 @@ __global__ __launch_bounds__(kEbcThreads) void ebc_sumsq_kernel(const TIn *__res
   red[threadIdx.x] = acc;
   __syncthreads();
   for (int s = kEbcThreads / 2; s > 0; s >>= 1) {
-    if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
     __syncthreads();
   }
   if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(kEbcThreads) void ebc_finish_kernel(const double *_
     red[threadIdx.x] = acc;
     __syncthreads();
     for (int s = kEbcThreads / 2; s > 0; s >>= 1) {
-      if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+      if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
       __syncthreads();
     }
     if (threadIdx.x == 0) sums[k] = red[0];
