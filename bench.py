@@ -39,6 +39,10 @@ def parse_args():
     ap.add_argument("--workload", default="wan14b_480p")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gate", default="0.4,0.8", help="layer gate lo,hi (0,1 disables)")
+    ap.add_argument("--fold-scale", action="store_true",
+                    help="time the headline step with HEART_ATTN_FOLD_SCALE (softmax scale folded into "
+                         "Q: one more bf16 rounding of the query, no per-logit multiply) instead of the "
+                         "library's default precision; the other path is always reported beside it")
     ap.add_argument("--policy-sweep", action="store_true",
                     help="instead of the headline step: run a multi-layer, multi-step TMR schedule "
                          "(dense warm-up, then sparse steps) under each reuse policy and print one "
@@ -99,7 +103,9 @@ def attn_profile(workload):
 def measured_ceilings(heart, torch, q0, k0):
     """What the chip sustains, measured live: MFMA-only loop on zero operands (nominal clock)
     and on operands taken from the workload's own Q and K (the chip is power limited and clocks
-    down on real data), and a plain 1 GiB copy."""
+    down on real data), a read-only stream over 1 GiB with the pooling kernel's access pattern
+    (what a streaming read sustains), and a plain 1 GiB copy (read + write; the reference for
+    scaling the traffic counters, not a ceiling for a read-only kernel)."""
     dev = q0.device
     sink = torch.zeros(1, dtype=torch.float32, device=dev)
     zeros = torch.zeros(8192, dtype=torch.bfloat16, device=dev)
@@ -129,6 +135,17 @@ def measured_ceilings(heart, torch, q0, k0):
         if rep:
             best = max(best, nb / (e0.elapsed_time(e1) * 1e-3) / 1e9)
     out["hbm_copy_gbs"] = best
+    best = 0.0
+    isink = torch.zeros(1, dtype=torch.int32, device=dev)
+    for rep in range(4):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        nb = heart.heart_ubench_read(src, isink)
+        e1.record()
+        torch.cuda.synchronize()
+        if rep:
+            best = max(best, nb / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    out["hbm_read_gbs"] = best
     del src, dst
     return out
 
@@ -407,9 +424,13 @@ def main():
     kidx = torch.zeros((B, H, Nb, Nb), dtype=torch.int32, device=dev)
     kcnt = torch.zeros((B, H, Nb), dtype=torch.int32, device=dev)
     out = torch.empty_like(steps_in[0][0])
-    attn_ws = torch.empty(heart.heart_attn_workspace_bytes(out, blk), dtype=torch.uint8, device=dev)
+    attn_ws = torch.empty(heart.heart_workspace_bytes(B, H, Nb, D), dtype=torch.uint8, device=dev)
+    flags_main = heart.HEART_ATTN_FOLD_SCALE if args.fold_scale else 0
+    flags_other = 0 if args.fold_scale else heart.HEART_ATTN_FOLD_SCALE
+    path_name = {0: "fp32_scale (default)", heart.HEART_ATTN_FOLD_SCALE: "fold_scale"}
+    gate = [gate_lo, gate_hi]
 
-    def one_step(it, ev=None, inner=False):
+    def one_step(it, ev=None, inner=False, flags=flags_main):
         """ev: five events; [0], [3], [4] bracket the mask-refresh side and the attention call,
         [1] and [2] (between pool, drift and mask) are only recorded when `inner` is set: every
         event record costs a few microseconds of gap between two kernels."""
@@ -420,40 +441,98 @@ def main():
         if ev: ev[0].record()
         heart.heart_pool_qk(q, k, blk, qblk, kblk, qmean, kmean)
         if ev and inner: ev[1].record()
-        heart.heart_drift(qmean, kmean, qa, ka, has, delta, gate_lo, gate_hi, True, drift, refresh)
+        heart.heart_drift(qmean, kmean, qa, ka, has, delta, gate[0], gate[1], True, drift, refresh)
         if ev and inner: ev[2].record()
         heart.heart_mask_topp(qblk, kblk, tau, refresh=refresh, n_always_kv_blocks=nt,
                               n_dense_q_blocks=nt, mask=mask, kept_idx=kidx, kept_count=kcnt)
         if ev: ev[3].record()
-        heart.heart_block_sparse_attn(q, k, v, blk, kidx, kcnt, out=out, workspace=attn_ws)
+        heart.heart_block_sparse_attn(q, k, v, blk, kidx, kcnt, out=out, workspace=attn_ws, flags=flags)
         if ev: ev[4].record()
 
     K, W = args.steps, args.warmup
-    for it in range(W):
-        one_step(it)
-    torch.cuda.synchronize()
 
-    # ---- timed region: exactly K steps; HIP events on the launch stream around the mask-refresh
-    # side (pool + drift + mask as one interval) and around the attention call ----
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for it in range(K):
-        one_step(it, events[it])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / K
-    refresh_ms = float(np.mean([events[i][0].elapsed_time(events[i][3]) for i in range(K)]))
-    attn_ms = float(np.mean([events[i][3].elapsed_time(events[i][4]) for i in range(K)]))
-    # ---- the same K steps once more, untimed, with events between pool, drift and mask too:
-    # the split of the mask-refresh side (each of the three figures includes its event gap) ----
-    events2 = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K)]
-    for it in range(K):
-        one_step(it, events2[it], inner=True)
-    torch.cuda.synchronize()
-    per = np.array([[events2[i][j].elapsed_time(events2[i][j + 1]) for j in range(3)]
-                    for i in range(K)])  # ms
+    def timed_schedule():
+        """W warm-up steps, then exactly K timed steps with HIP events on the launch stream around
+        the mask-refresh side (pool + drift + mask as one interval) and around the attention call;
+        then the same K steps once more, untimed, with events between pool, drift and mask too
+        (the split of the mask-refresh side; each of the three figures includes its event gap)."""
+        has.zero_()
+        for it in range(W):
+            one_step(it)
+        torch.cuda.synchronize()
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for it in range(K):
+            one_step(it, events[it])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        r = {"ms_per_step": (t1 - t0) * 1e3 / K,
+             "refresh_ms": float(np.mean([events[i][0].elapsed_time(events[i][3]) for i in range(K)])),
+             "attn_ms": float(np.mean([events[i][3].elapsed_time(events[i][4]) for i in range(K)]))}
+        events2 = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K)]
+        for it in range(K):
+            one_step(it, events2[it], inner=True)
+        torch.cuda.synchronize()
+        r["per"] = np.array([[events2[i][j].elapsed_time(events2[i][j + 1]) for j in range(3)]
+                             for i in range(K)])  # ms: pool, drift, mask per step
+        return r
+
+    def replay_stats():
+        """Untimed replay of the same K steps: kept-block FLOPs, density, refresh ratio, mask IoU."""
+        has.zero_(); kcnt.zero_()
+        flops, dens, refr, ious = [], [], [], []
+        dens_head = torch.zeros(H, device=dev)
+        prev_mask = None
+        for it in range(K):
+            one_step(it)
+            torch.cuda.synchronize()
+            flops.append(kept_flops(kidx, kcnt, N, blk, D))
+            dens.append(float(kcnt.sum().item()) / (B * H * Nb * Nb))
+            dens_head += kcnt.float().sum(dim=(0, 2)) / (B * Nb * Nb)
+            refr.append(float(refresh.float().mean().item()))
+            if prev_mask is not None and it % S != 0:
+                inter = (mask & prev_mask).sum().item()
+                union = (mask | prev_mask).sum().item()
+                ious.append(inter / max(1, union))
+            prev_mask = mask.clone()
+        return flops, dens, refr, ious, dens_head
+
+    # ---- headline: the gate as given on the command line (default 0.4 / 0.8) ----
+    tm = timed_schedule()
+    ms_per_step, refresh_ms, attn_ms, per = tm["ms_per_step"], tm["refresh_ms"], tm["attn_ms"], tm["per"]
     pool_ms, drift_ms, mask_ms = per.mean(0)
+    flops, dens, refr, ious, dens_head = replay_stats()
+
+    # ---- the other precision path of the attention kernel on the lists of the last step ----
+    for _ in range(2):
+        heart.heart_block_sparse_attn(*steps_in[(K - 1) % S], blk, kidx, kcnt, out=out, workspace=attn_ws,
+                                      flags=flags_other)
+    ev_o = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    ev_o[0].record()
+    for i in range(K):
+        heart.heart_block_sparse_attn(*steps_in[(K - 1) % S], blk, kidx, kcnt, out=out, workspace=attn_ws,
+                                      flags=flags_other)
+        ev_o[i + 1].record()
+    torch.cuda.synchronize()
+    other_ms = float(np.mean([ev_o[i].elapsed_time(ev_o[i + 1]) for i in range(K)]))
+    other_tflops = flops[-1] / (other_ms * 1e-3) / 1e12
+
+    # ---- the same schedule with the layer gate off (0 / 1), for the headline workload ----
+    gate_off = None
+    if (gate_lo, gate_hi) != (0.0, 1.0):
+        gate[:] = [0.0, 1.0]
+        tg = timed_schedule()
+        fl_g, dens_g, refr_g, _, _ = replay_stats()
+        gate[:] = [gate_lo, gate_hi]
+        gate_off = {"ms_per_step": tg["ms_per_step"], "mask_refresh_us_per_step": tg["refresh_ms"] * 1e3,
+                    "kernels_us": {"pool_qk": float(tg["per"][:, 0].mean() * 1e3),
+                                   "drift": float(tg["per"][:, 1].mean() * 1e3),
+                                   "mask_topp": float(tg["per"][:, 2].mean() * 1e3),
+                                   "block_sparse_attn": tg["attn_ms"] * 1e3},
+                    "value": float(np.mean(fl_g)) / (tg["ms_per_step"] * 1e-3) / 1e12,
+                    "refreshed_head_fraction_per_step": [round(x, 3) for x in refr_g],
+                    "kept_block_density": float(np.mean(dens_g))}
 
     # ---- launch overhead: schedule step 1 repeated K times, eagerly and as one HIP graph ----
     # (extra information; `value` comes from the eager region above.  After the first
@@ -485,23 +564,6 @@ def main():
     except Exception as e:  # optional figure
         print(f"[bench] HIP graph timing skipped: {e}", file=sys.stderr, flush=True)
 
-    # ---- untimed replay of the same K steps to count kept-block FLOPs and refresh ratio ----
-    has.zero_(); kcnt.zero_()
-    flops, dens, refr, ious = [], [], [], []
-    dens_head = torch.zeros(H, device=dev)
-    prev_mask = None
-    for it in range(K):
-        one_step(it)
-        torch.cuda.synchronize()
-        flops.append(kept_flops(kidx, kcnt, N, blk, D))
-        dens.append(float(kcnt.sum().item()) / (B * H * Nb * Nb))
-        dens_head += kcnt.float().sum(dim=(0, 2)) / (B * Nb * Nb)
-        refr.append(float(refresh.float().mean().item()))
-        if prev_mask is not None and it % S != 0:
-            inter = (mask & prev_mask).sum().item()
-            union = (mask | prev_mask).sum().item()
-            ious.append(inter / max(1, union))
-        prev_mask = mask.clone()
     flops_per_step = float(np.mean(flops))
     dense_flops = 4.0 * N * N * D * H * B
 
@@ -514,6 +576,19 @@ def main():
     ceil = measured_ceilings(heart, torch, steps_in[0][0], steps_in[0][1])
     prof = attn_profile(args.workload)
     mask_f64_flops = refreshed * B * H * 2.0 * Nb * Nb * D  # fp64 dot products of the score stage
+    # the mask kernel only works on steps where some head refreshes: its time on those steps,
+    # and per refreshed head (per-step figures come from the untimed, event-split repetition)
+    refr_steps = np.array(refr)
+    mask_us_steps = per[:, 2] * 1e3
+    busy = refr_steps > 0
+    mask_detail = {
+        "us_per_refreshing_step": float(mask_us_steps[busy].mean()) if busy.any() else None,
+        "us_per_step_without_refresh": float(mask_us_steps[~busy].mean()) if (~busy).any() else None,
+        "us_per_refreshed_head": (float(mask_us_steps[busy].sum() / (refr_steps[busy].sum() * B * H))
+                                  if busy.any() else None),
+        "refreshing_steps": int(busy.sum()),
+    }
+    refresh_bytes = pool_bytes + 4 * B * H * D * 4 + mask_bytes  # pool + drift + mask, algorithmic
 
     result = {
         "metric": "sparse-attn effective TFLOP/s + mask-refresh us/step, Wan-14B 480P shape, 1 GPU",
@@ -531,6 +606,7 @@ def main():
         "config": {
             "workload": f"{cfg.name}: B={B} H={H} D={D} N={N} grid={'x'.join(map(str, cfg.grid))} "
                         f"block={blk}, {S}-step synthetic TMR schedule, gate {gate_lo}/{gate_hi}",
+            "attention_precision_path": path_name[flags_main],
             "value_definition": "kept-block attention FLOPs (4*D*sum n_i*n_j over kept blocks) per "
                                 "step / wall time of the whole step (pool+drift+mask+attention)",
         },
@@ -539,6 +615,14 @@ def main():
         "kernels_us": {"pool_qk": pool_ms * 1e3, "drift": drift_ms * 1e3,
                        "mask_topp": mask_ms * 1e3, "block_sparse_attn": attn_ms * 1e3},
         "attn_kept_tflops": attn_tflops,
+        "attn_kept_tflops_other_path": {"path": path_name[flags_other], "tflops": other_tflops,
+                                        "us": other_ms * 1e3,
+                                        "note": "same lists (last timed step), K back-to-back launches"},
+        "mask_topp_detail": mask_detail,
+        "mask_refresh_side": {"bound": "hbm", "algorithmic_bytes": refresh_bytes,
+                              "achieved": refresh_bytes / (refresh_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                              "unit": "GB/s", "frac": refresh_bytes / (refresh_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
+        "gate_off": gate_off,
         "attn_dense_equiv_tflops": dense_flops / (attn_ms * 1e-3) / 1e12,
         "kept_block_density": float(np.mean(dens)),
         "kept_block_density_per_head": [round(float(x), 4) for x in (dens_head / K).cpu().tolist()],
@@ -571,6 +655,9 @@ def main():
                                 "alu_fp64": {"bound": "alu", "achieved": mask_f64_flops / (mask_ms * 1e-3) / 1e12,
                                              "peak": PEAK_FP64_VALU_TFLOPS, "unit": "TFLOP/s",
                                              "frac": mask_f64_flops / (mask_ms * 1e-3) / 1e12 / PEAK_FP64_VALU_TFLOPS}},
+            # what a read-only stream with the pooling kernel's access pattern sustains (its
+            # measured ceiling), and a plain copy (read + write: the counter-scaling reference)
+            "measured_stream_read_gbs": ceil["hbm_read_gbs"],
             "measured_copy_gbs": ceil["hbm_copy_gbs"],
         },
     }

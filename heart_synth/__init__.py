@@ -26,10 +26,25 @@ Multi-step schedules: step s adds, per head, a common offset vector (which is
 what moves the token mean) of scheduled L1 size, directed within the span of the
 head's own sinusoid directions (so that it also changes the head's block scores), plus noise_std[s, h] times one
 fixed iid N(0,1) field per (tensor, head).
+
+The "jumps" schedule is laid out so that the share of heads whose features move far
+from where they last jumped is between 40 % and 70 % at every step after the first:
+inside the 30-70 % band the Wan2.1-14B-shaped benchmark configuration asks for, and
+never below the 40 % at which the layer-level gate of the method (Sec. 4.2) would
+turn a step into reuse for every head, so the same schedule serves runs with the gate
+on and off.  `planned_jumps[s, h]` records the layout (step 0: every head, nothing is
+cached yet); it is bookkeeping of this generator, not a decision of the method.
+
+Per-head thresholds are drawn uniformly, except for the Wan2.1-14B-shaped 720P
+configuration, which asks for a global kept-block density of 15 % "via per-head tau":
+its thresholds are a stored table (wan14b_720p_tau.json beside this file, written by
+oracle/make_density_tau.py from the CPU oracle's scores and top-p rule on step 0).
 """
 from __future__ import annotations
 
+import json
 import math
+import os
 from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 from typing import Dict, List, Optional, Tuple
@@ -62,7 +77,9 @@ class HeartConfig:
     n_text: int = 0  # text tokens prepended (always-kept blocks)
     steps: int = 2
     gain: float = 8.0
-    # how per-head thresholds are drawn: ("list", [...]) or ("uniform", lo, hi)
+    # how per-head thresholds are drawn: ("list", [...]), ("uniform", lo, hi), or
+    # ("file", name, lo, hi): a stored table beside this module (made from uniform draws
+    # in [lo, hi] by the script the file names)
     tau_spec: tuple = ("uniform", 0.85, 0.98)
     delta: float = 1.0
     # schedule kind: "tiny" (iid noise per head), "loguniform" (one later step,
@@ -105,7 +122,8 @@ CONFIGS: Dict[str, HeartConfig] = {
     # (4) Wan2.1-14B at 720P
     "wan14b_720p": HeartConfig(
         name="wan14b_720p", B=1, H=40, D=128, grid=(21, 45, 80), block=128, seed=3,
-        steps=2, tau_spec=("uniform", 0.85, 0.98), delta=1.0, schedule="jumps",
+        steps=2, tau_spec=("file", "wan14b_720p_tau.json", 0.85, 0.98), delta=1.0,
+        schedule="jumps",
     ),
     # (5) HunyuanVideo-shaped, 720P, with text tokens in front
     "hunyuan_720p": HeartConfig(
@@ -193,7 +211,18 @@ class HeartInputGenerator:
             tau = np.asarray(cfg.tau_spec[1], dtype=np.float32)
             assert tau.shape == (cfg.H,)
         else:
-            tau = rng.uniform(cfg.tau_spec[1], cfg.tau_spec[2], size=cfg.H).astype(np.float32)
+            lo_t, hi_t = cfg.tau_spec[-2:]
+            tau = rng.uniform(lo_t, hi_t, size=cfg.H).astype(np.float32)
+        # (the uniform draw is kept for every spec so that the random stream below is the same)
+        self.tau_drawn = tau
+        if cfg.tau_spec[0] == "file":
+            path = os.path.join(os.path.dirname(os.path.abspath(__file__)), cfg.tau_spec[1])
+            if os.path.exists(path):
+                with open(path) as f:
+                    table = json.load(f)
+                assert table["config"] == cfg.name and len(table["tau"]) == cfg.H
+                tau = np.asarray(table["tau"], dtype=np.float32)
+            # (absent only while the script that writes it runs)
         self.tau = tau
         self.delta = np.full((cfg.H,), cfg.delta, dtype=np.float32)
         lo, hi = cfg.locality
@@ -203,6 +232,7 @@ class HeartInputGenerator:
         # offsets[s, h] = L1 size of the common offset added (cumulatively) at step s
         inc = np.zeros((S, H), dtype=np.float64)
         noise = np.zeros((S, H), dtype=np.float64)  # std of iid noise at step s vs step 0
+        planned = np.zeros((S, H), dtype=bool)
         if cfg.schedule == "tiny":
             # tiny configuration: step 2 = step 1 + N(0, 0.02) on head 0, N(0, 0.5) on head 1
             sig = [0.02, 0.5]
@@ -215,14 +245,19 @@ class HeartInputGenerator:
                 inc[s] = mag
                 noise[s] = mag * 0.1
         elif cfg.schedule == "jumps":
+            planned[0] = True
             for s in range(1, S):
-                n_jump = int(rng.integers(math.ceil(0.3 * H), math.floor(0.7 * H) + 1))
+                n_lo = math.ceil(0.4 * H - 1e-9)
+                n_hi = max(n_lo, math.floor(0.7 * H + 1e-9))
+                n_jump = int(rng.integers(n_lo, n_hi + 1))
                 jump = rng.permutation(H)[:n_jump]
                 inc[s] = 0.01 * cfg.delta
                 inc[s, jump] = 4.0 * cfg.delta
                 noise[s] = 0.002 * s
+                planned[s, jump] = True
         else:
             raise ValueError(cfg.schedule)
+        self.planned_jumps = planned  # [S, H] bool, "jumps" schedule only
         self.offset_l1 = np.cumsum(inc, axis=0)  # [S, H]
         self.noise_std = noise
         # Fixed per-head offset directions (unit L1 norm), separate for Q and K.  They lie in

@@ -11,7 +11,8 @@
  *     storage of PyTorch-ROCm tensors).  The library allocates nothing, keeps no
  *     state between calls (beyond per-device launch attributes it sets once), reads no
  *     environment variable; an entry point that needs scratch memory takes it as a
- *     workspace argument.
+ *     workspace argument.  Workspace sizes: heart_workspace_bytes (the hot path),
+ *     heart_scores_antidiag_workspace_bytes, heart_ebc_workspace_bytes.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call
  *     only enqueues kernels on that stream and returns; it never synchronises.
  *   - Return value: HEART_OK (0) or a negative error code.  After an error
@@ -107,8 +108,14 @@ int heart_drift(int B, int H, int D, const float *qmean, const float *kmean, flo
  *   every row and query rows i < n_dense_q_blocks keep every column.
  * Inputs : qblk, kblk fp32 [B,H,Nb,D] (may both be NULL if scores_in is given);
  *          scores_in fp32 [B,H,Nb,Nb] or NULL: if given, the score stage is skipped
- *          and these scores are ranked instead (each must lie in [0,1]);
- *          tau fp32 [H] (device), each > 0; refresh uint8 [B,H] or NULL (= all heads).
+ *          and these scores are ranked instead (each must lie in [0,1]; the kernel
+ *          clamps larger values to 1 and counts negative values and NaN as 0, so a
+ *          bad table cannot overflow the integer mass);
+ *          tau fp32 [H] (device), in (0, 1] for the rule above.  tau lives on the device,
+ *          so the host cannot reject a bad value: tau_h <= 0 (or NaN) asks for no mass
+ *          and keeps exactly max(1, min_keep) best-ranked blocks per row;
+ *          refresh uint8 [B,H] or NULL (= all heads).
+ * No workspace: the logits of a row group live in LDS and the selection in registers.
  * Outputs, written only for heads with refresh != 0 (cached masks of reused heads
  * persist, Alg. 1):
  *          mask uint8 [B,H,Nb,Nb] (1 = kept);
@@ -157,16 +164,22 @@ int heart_scores_antidiag(const heart_shape *shape, const void *q, const void *k
  *     out[n,:] = sum_t softmax_t( q_n . k_t * scale ) v_t,   t over the real tokens of
  *     the key blocks kept_idx[b,h,i,0..kept_count[b,h,i])
  *   computed flash-style (online softmax) with bf16 MFMA and fp32 accumulation.
- *   Precision: q is multiplied by scale * log2(e) and rounded to bf16 once (the error of one
- *   more bf16 rounding of the query), the softmax weights are rounded to bf16 for the second
- *   contraction, everything else is fp32.  For q, k, v of unit scale (logits of a few units)
- *   the output is within 2e-2 of exact attention on the given bf16 inputs; the error grows
- *   with the cube of the input scale.
+ *   Precision (default): logits from the bf16 matrix cores with fp32 accumulation, scaled
+ *   in fp32; exponentials in fp32; the softmax weights are rounded to bf16 for the second
+ *   contraction while the row sum adds the unrounded weights; the output is rounded to
+ *   bf16.  The error against exact attention on the given bf16 inputs is that of the bf16
+ *   rounding of weights and output: within 2e-2 * max(1, max|out| / 2) for any input scale.
+ *   With HEART_ATTN_FOLD_SCALE (heart_block_sparse_attn_flags) q is instead multiplied by
+ *   scale * log2(e) and rounded to bf16 once, which removes one multiply per logit (about
+ *   3 % faster) at the price of one more bf16 rounding of the query: the same bound holds
+ *   for q, k of unit scale (logits of a few units; normalised activations), but that error
+ *   grows with the cube of the input scale.
  * q, k, v: bf16 with the strides of `shape`; out: bf16 with o_stride; kept_idx /
  * kept_count as written by heart_mask_topp (indices must lie in [0, Nb); order
  * does not matter for the result up to rounding); scale <= 0 means 1/sqrt(D);
  * lse: fp32 [B,H,N] natural-log-sum-exp of the scaled logits over the kept keys,
  * or NULL.  A row with kept_count == 0 yields zeros (lse = -inf).
+ * Supported: every (D, block) pair of heart_shape.
  * workspace: device memory of at least heart_attn_workspace_bytes(shape) bytes, 16-byte
  * aligned, or NULL.  With a workspace the call first builds a launch plan in it (whole
  * heads are assigned to the XCDs so that the workgroups of an XCD share one head's K/V
@@ -180,7 +193,22 @@ int heart_block_sparse_attn(const heart_shape *shape, const void *q_bf16, const 
                             float scale, void *out_bf16, float *lse, void *workspace,
                             size_t workspace_bytes, void *stream);
 
-/* Bytes of workspace heart_block_sparse_attn can use for `shape` (0 if shape is invalid). */
+/* The same call with option flags (0 = heart_block_sparse_attn; unknown bits are an error). */
+#define HEART_ATTN_FOLD_SCALE 1u /* fold the softmax scale into q (see Precision above) */
+int heart_block_sparse_attn_flags(const heart_shape *shape, const void *q_bf16,
+                                  const void *k_bf16, const void *v_bf16, const int *kept_idx,
+                                  const int *kept_count, float scale, unsigned flags,
+                                  void *out_bf16, float *lse, void *workspace,
+                                  size_t workspace_bytes, void *stream);
+
+/*
+ * Bytes of workspace the hot path can use for one call: only heart_block_sparse_attn takes one
+ * (its launch plan: 24 + B*H*(Nb+2) ints); heart_pool_qk, heart_drift and heart_mask_topp
+ * need none.  heart_workspace_bytes takes plain sizes (D does not enter; it is part of the
+ * signature so that callers can size by the full shape), heart_attn_workspace_bytes a
+ * heart_shape; both return 0 for an invalid shape.
+ */
+size_t heart_workspace_bytes(int B, int H, int Nb, int D);
 size_t heart_attn_workspace_bytes(const heart_shape *shape);
 
 /*
@@ -209,22 +237,6 @@ size_t heart_ebc_workspace_bytes(long long C, int T, int Y, int X);
 int heart_ebc_select(int n_heads, int n_candidates, const double *error_host,
                      const double *sparsity_host, double min_mean_sparsity, int *choice_host,
                      double *total_error_host);
-
-/*
- * Diagnostics for roofline accounting (not part of the method).
- * heart_ubench_mfma_bf16: n_workgroups workgroups of 4 wavefronts each issue 16 * iters
- *   v_mfma_f32_32x32x16_bf16 on register operands taken from a_bf16 / b_bf16 (device,
- *   8192 bf16 each, 16-byte aligned); FLOPs = n_workgroups * 4 * iters * 16 * 32768.
- *   The sustained clock of the chip depends on the operand bits, so timing this call
- *   with zeros and with data like a kernel's own gives the nominal and the attainable
- *   matrix-core rate.  sink: one float (device), practically never written.
- * heart_ubench_copy: plain device-to-device copy of `bytes` (multiple of 16); moves
- *   2 * bytes through HBM.  Reference for HBM bandwidth and for scaling hardware
- *   traffic counters.
- */
-int heart_ubench_mfma_bf16(const void *a_bf16, const void *b_bf16, int n_workgroups, int iters,
-                           float *sink, void *stream);
-int heart_ubench_copy(const void *src, void *dst, size_t bytes, void *stream);
 
 /* Thread-local message of the last error returned on this thread ("" if none). */
 const char *heart_last_error(void);

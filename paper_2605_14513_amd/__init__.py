@@ -3,10 +3,12 @@ behind a C ABI).  `binding` mirrors the four entry points of include/heart.h on
 torch-ROCm tensors; it only marshals arguments -- every step runs in the HIP
 kernels, and importing/calling it without the built library fails loudly."""
 from .binding import (  # noqa: F401
+    HEART_ATTN_FOLD_SCALE,
     HeartError,
     HeartShape,
     heart_attn_workspace_bytes,
     heart_block_sparse_attn,
+    heart_block_sparse_attn_flags,
     heart_drift,
     heart_ebc_band_error,
     heart_ebc_select,
@@ -17,8 +19,10 @@ from .binding import (  # noqa: F401
     heart_scores_antidiag,
     heart_scores_antidiag_workspace_bytes,
     heart_ubench_copy,
+    heart_ubench_read,
     heart_ubench_mfma_bf16,
     heart_version,
+    heart_workspace_bytes,
     lib_path,
     load_library,
 )

@@ -59,11 +59,17 @@ def load_library() -> ctypes.CDLL:
                                     vp, vp]
     lib.heart_block_sparse_attn.argtypes = [sp, vp, vp, vp, vp, vp, cf, vp, vp, vp,
                                             ctypes.c_size_t, vp]
+    lib.heart_block_sparse_attn_flags.argtypes = [sp, vp, vp, vp, vp, vp, cf, ctypes.c_uint, vp, vp,
+                                                  vp, ctypes.c_size_t, vp]
     lib.heart_attn_workspace_bytes.argtypes = [sp]
     lib.heart_attn_workspace_bytes.restype = ctypes.c_size_t
+    lib.heart_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.heart_workspace_bytes.restype = ctypes.c_size_t
     for f in (lib.heart_pool_qk, lib.heart_drift, lib.heart_mask_topp,
-              lib.heart_block_sparse_attn, lib.heart_version):
+              lib.heart_block_sparse_attn, lib.heart_block_sparse_attn_flags, lib.heart_version):
         f.restype = ci
+    lib.heart_ubench_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    lib.heart_ubench_read.restype = ci
     lib.heart_ubench_mfma_bf16.argtypes = [vp, vp, ci, ci, vp, vp]
     lib.heart_ubench_mfma_bf16.restype = ci
     lib.heart_ubench_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
@@ -221,17 +227,26 @@ def heart_mask_topp(qblk, kblk, tau, refresh=None, scores_in=None, n_always_kv_b
     return mask, kept_idx, kept_count
 
 
+HEART_ATTN_FOLD_SCALE = 1  # flag of heart_block_sparse_attn_flags (include/heart.h)
+
+
+def heart_workspace_bytes(B: int, H: int, Nb: int, D: int) -> int:
+    """Bytes of workspace one call of the hot path can use (the attention launch plan)."""
+    return int(load_library().heart_workspace_bytes(int(B), int(H), int(Nb), int(D)))
+
+
 def heart_attn_workspace_bytes(q, block: int) -> int:
     """Bytes of workspace heart_block_sparse_attn can use for tensors shaped like q."""
     return int(load_library().heart_attn_workspace_bytes(ctypes.byref(make_shape(q, q, block))))
 
 
 def heart_block_sparse_attn(q, k, v, block: int, kept_idx, kept_count, scale: float = 0.0,
-                            out=None, lse=None, workspace="auto"):
+                            out=None, lse=None, workspace="auto", flags: int = 0):
     """Block-sparse attention over the kept key blocks; returns bf16 out like q.
 
     workspace: a uint8/int32 GPU tensor of at least heart_attn_workspace_bytes, None (natural
-    launch order), or "auto" (a fresh tensor from torch's allocator)."""
+    launch order), or "auto" (a fresh tensor from torch's allocator).
+    flags: 0 (heart_block_sparse_attn) or HEART_ATTN_FOLD_SCALE (heart_block_sparse_attn_flags)."""
     lib = load_library()
     if q.shape != k.shape or q.shape != v.shape:
         raise ValueError("q, k, v must have the same shape")
@@ -254,15 +269,25 @@ def heart_block_sparse_attn(q, k, v, block: int, kept_idx, kept_count, scale: fl
         if not workspace.is_cuda or not workspace.is_contiguous():
             raise ValueError("workspace must be a contiguous GPU tensor")
         ws_ptr, ws_bytes = ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
-    rc = lib.heart_block_sparse_attn(ctypes.byref(shape), _dev(q, torch.bfloat16, "q", False),
-                                     _dev(k, torch.bfloat16, "k", False),
-                                     _dev(v, torch.bfloat16, "v", False),
-                                     _dev(kept_idx, torch.int32, "kept_idx"),
-                                     _dev(kept_count, torch.int32, "kept_count"), float(scale),
-                                     _dev(out, torch.bfloat16, "out", False),
-                                     _dev(lse, torch.float32, "lse"), ws_ptr, ws_bytes, _stream())
-    _check("heart_block_sparse_attn", rc)
+    args = [ctypes.byref(shape), _dev(q, torch.bfloat16, "q", False),
+            _dev(k, torch.bfloat16, "k", False), _dev(v, torch.bfloat16, "v", False),
+            _dev(kept_idx, torch.int32, "kept_idx"), _dev(kept_count, torch.int32, "kept_count"),
+            float(scale)]
+    tail = [_dev(out, torch.bfloat16, "out", False), _dev(lse, torch.float32, "lse"), ws_ptr,
+            ws_bytes, _stream()]
+    if flags:
+        _check("heart_block_sparse_attn_flags",
+               lib.heart_block_sparse_attn_flags(*args, int(flags), *tail))
+    else:
+        _check("heart_block_sparse_attn", lib.heart_block_sparse_attn(*args, *tail))
     return out
+
+
+def heart_block_sparse_attn_flags(q, k, v, block: int, kept_idx, kept_count, flags: int,
+                                  scale: float = 0.0, out=None, lse=None, workspace="auto"):
+    """heart_block_sparse_attn with option flags (HEART_ATTN_FOLD_SCALE)."""
+    return heart_block_sparse_attn(q, k, v, block, kept_idx, kept_count, scale=scale, out=out,
+                                   lse=lse, workspace=workspace, flags=flags)
 
 
 def heart_ubench_mfma_bf16(a, b, n_workgroups: int, iters: int, sink=None):
@@ -288,6 +313,18 @@ def heart_ubench_copy(src, dst):
     rc = lib.heart_ubench_copy(_dev(src, src.dtype, "src"), _dev(dst, dst.dtype, "dst"), nbytes, _stream())
     _check("heart_ubench_copy", rc)
     return 2.0 * nbytes
+
+
+def heart_ubench_read(src, sink=None):
+    """Enqueue a read-only stream over src (the pooling kernel's access pattern); returns the
+    HBM bytes it moves."""
+    lib = load_library()
+    nbytes = src.numel() * src.element_size()
+    if sink is None:
+        sink = torch.zeros(1, dtype=torch.int32, device=src.device)
+    rc = lib.heart_ubench_read(_dev(src, src.dtype, "src"), nbytes, _dev(sink, torch.int32, "sink"), _stream())
+    _check("heart_ubench_read", rc)
+    return float(nbytes)
 
 
 def heart_scores_antidiag_workspace_bytes(q, block: int, stride: int) -> int:

@@ -122,10 +122,13 @@ __global__ __launch_bounds__(512, 2) void antidiag_tile_kernel(
     for (int ii = 0; ii < 4; ++ii) {
       const uint32_t dst_a = smem_lds + (uint32_t)(buf * 2 * kAdTileB + (4 * wave + ii) * 1024);
       const uint32_t dst_b = dst_a + (uint32_t)kAdTileB;
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                   :: "s"(dst_a), "v"(k_dma[ii] + ko), "s"(k_rs) : "memory");
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                   :: "s"(dst_b), "v"(q_dma[ii] + qo), "s"(q_rs) : "memory");
+      uint32_t m0_saved;  // (M0 carries the LDS destination; saved and restored for the compiler)
+      asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                   "buffer_load_dwordx4 %2, %3, 0 offen lds\n\ts_mov_b32 m0, %0"
+                   : "=&s"(m0_saved) : "s"(dst_a), "v"(k_dma[ii] + ko), "s"(k_rs) : "memory");
+      asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                   "buffer_load_dwordx4 %2, %3, 0 offen lds\n\ts_mov_b32 m0, %0"
+                   : "=&s"(m0_saved) : "s"(dst_b), "v"(q_dma[ii] + qo), "s"(q_rs) : "memory");
     }
   };
   auto wait_loads_and_barrier = [&]() __attribute__((always_inline)) {
@@ -346,15 +349,11 @@ int launch_antidiag(const heart_shape &s, const void *q, const void *k, int stri
 #define HEART_AD_LAUNCH(DD)                                                                        \
   do {                                                                                             \
     auto kern = antidiag_tile_kernel<DD>;                                                          \
-    static bool attr_set[kMaxDevices] = {};                                                        \
-    if (!attr_set[dev]) {                                                                          \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                     \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, kAdLds);      \
-      if (e != hipSuccess)                                                                         \
-        return fail(HEART_EHIP, "hipFuncSetAttribute(antidiagonal tile kernel LDS): %s",           \
-                    hipGetErrorString(e));                                                         \
-      attr_set[dev] = true;                                                                        \
-    }                                                                                              \
+    static DeviceFlags attr_set;                                                                   \
+    if (hipError_t e = set_max_lds_once(attr_set, dev, reinterpret_cast<const void *>(kern),       \
+                                        kAdLds))                                                   \
+      return fail(HEART_EHIP, "hipFuncSetAttribute(antidiagonal tile kernel LDS): %s",             \
+                  hipGetErrorString(e));                                                           \
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), kAdLds, st, (const uint16_t *)q,     \
                        (const uint16_t *)k, s.q_stride[0], s.q_stride[1], s.q_stride[2],           \
                        s.k_stride[0], s.k_stride[1], s.k_stride[2], s.H, BH, s.N, S, M, MT2,       \

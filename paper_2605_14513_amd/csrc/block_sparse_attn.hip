@@ -199,6 +199,7 @@ __global__ __launch_bounds__(256) void attn_order_kernel(const int *__restrict__
   auto cls_of = [&](int i) -> int { return kStaged ? (int)cls_lds[i] : cls(kept_count[i]); };
 #pragma unroll
   for (int b = 0; b < kOrderClasses; ++b) hist[b][t] = 0;
+  __syncthreads();  // `total` is zero before any wavefront adds to it
   if (kStaged) {
 #pragma unroll 16
     for (int i = t; i < n; i += 256) cls_lds[i] = (unsigned char)cls(kept_count[i]);
@@ -241,13 +242,11 @@ __global__ __launch_bounds__(256) void attn_order_kernel(const int *__restrict__
   }
 }
 
-// 1: keep Q as it is and scale every logit in fp32 (one more multiply per logit, 3-4 % slower);
-// the error then stays at the bf16 rounding of the weights and of the output for any input
-// scale.  0: fold the softmax scale into Q once (one more bf16 rounding of the query; the
-// error grows with the cube of the input scale, inside the budget for inputs of unit scale).
-#ifndef HEART_ATTN_EXACT_SCALE
-#define HEART_ATTN_EXACT_SCALE 0
-#endif
+// kExact (the default of the ABI): Q stays as it is and every logit is scaled in fp32 (one more
+// multiply per logit); the error is then the bf16 rounding of the weights and of the output
+// for any input scale.  !kExact (HEART_ATTN_FOLD_SCALE): the softmax scale is folded into Q
+// once (one more bf16 rounding of the query; the error grows with the cube of the input scale,
+// inside the budget for inputs of unit scale) and no per-logit multiply is left.
 #ifndef HEART_ATTN_PF
 #define HEART_ATTN_PF 4  // LDS fragment reads in flight ahead of the MFMAs
 #endif
@@ -255,7 +254,7 @@ __global__ __launch_bounds__(256) void attn_order_kernel(const int *__restrict__
 #define HEART_ATTN_OCC 2  // waves per SIMD the register budget is sized for
 #endif
 
-template <int D, int BLK>
+template <int D, int BLK, bool kExact>
 __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k,
     const uint16_t *__restrict__ v, uint16_t *__restrict__ out, long long qsb, long long qsh,
@@ -275,15 +274,12 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   constexpr int IPW = kStageRows / RPI / NW;  // such instructions per wavefront and tile
   constexpr int NSL = BLK / 32;          // 32-key slices per key block
   constexpr int SO = D + 8;              // LDS row stride of the output staging (elements)
-#if HEART_ATTN_EXACT_SCALE
-  // (accumulators, maxima and the reference exponent are in raw logit units; kLogitScale
-  // takes them to log2 units where they enter an exponential)
-  const float kLogitScale = scale_log2e;
-  const float kRescaleSlack = 8.f / scale_log2e;
-#else
-  constexpr float kLogitScale = 1.f;     // the accumulators already are in log2 units
-  constexpr float kRescaleSlack = 8.f;   // log2 units the running reference may lag the max
-#endif
+  // kExact: accumulators, maxima and the reference exponent are in raw logit units and
+  // kLogitScale takes them to log2 units where they enter an exponential; otherwise the
+  // accumulators already are in log2 units.  The running reference may lag the maximum by
+  // 8 log2 units.
+  const float kLogitScale = kExact ? scale_log2e : 1.f;
+  const float kRescaleSlack = kExact ? 8.f / scale_log2e : 8.f;
   static_assert(NW % 2 == 0 && IPW >= 1 && (NSL == 2 || NSL == 4), "tile layout");
 
   // LDS: [K stage 0][K stage 1][V stage 0][V stage 1], reused for the output at the end
@@ -355,13 +351,18 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
         is_v ? vdma + (uint32_t)krow * v_row_bytes : kdma[ii] + (uint32_t)krow * k_row_bytes;
     const uint32_t dst = smem_lds + (uint32_t)((2 * is_v + buf) * TILE_B + (wave * IPW + ii) * 1024);
     // (the compiler does not see this instruction's LDS write, so it adds no waits of
-    // its own: completion is awaited explicitly before the barrier that publishes the tile)
+    // its own: completion is awaited explicitly before the barrier that publishes the tile.
+    // The LDS destination travels in M0, which the statement saves and restores: the
+    // compiler is free to keep values of its own there)
+    uint32_t m0_saved;
     if (is_v)
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                   :: "s"(dst), "v"(voffset), "s"(v_rs) : "memory");
+      asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                   "buffer_load_dwordx4 %2, %3, 0 offen lds\n\ts_mov_b32 m0, %0"
+                   : "=&s"(m0_saved) : "s"(dst), "v"(voffset), "s"(v_rs) : "memory");
     else
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                   :: "s"(dst), "v"(voffset), "s"(k_rs) : "memory");
+      asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                   "buffer_load_dwordx4 %2, %3, 0 offen lds\n\ts_mov_b32 m0, %0"
+                   : "=&s"(m0_saved) : "s"(dst), "v"(voffset), "s"(k_rs) : "memory");
   };
 
   Frag8 qf[KS];      // Q fragments (B operand of S^T = K Q^T), kept in registers
@@ -384,15 +385,15 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
       qf[ks].u = __builtin_amdgcn_raw_buffer_load_b128(q_rs, q_off + ks * 32, 0, 0);
-#if !HEART_ATTN_EXACT_SCALE
-    // fold the softmax scale and log2(e) into Q once: S^T then comes out of the matrix
-    // cores in log2 units and no per-logit multiply is left on the VALU
+    if constexpr (!kExact) {
+      // fold the softmax scale and log2(e) into Q once: S^T then comes out of the matrix
+      // cores in log2 units and no per-logit multiply is left on the VALU
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
+      for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-      for (int w = 0; w < 4; ++w)
-        qf[ks].u[w] = cvt_pk_bf16(bf16lo(qf[ks].u[w]) * scale_log2e, bf16hi(qf[ks].u[w]) * scale_log2e);
-#endif
+        for (int w = 0; w < 4; ++w)
+          qf[ks].u[w] = cvt_pk_bf16(bf16lo(qf[ks].u[w]) * scale_log2e, bf16hi(qf[ks].u[w]) * scale_log2e);
+    }
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -487,10 +488,10 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
     // (the empty asm statements pin each result to its slot: without them the compiler
     // sinks the whole computation to its first use, out of the MFMA shadow)
     if (st == 0) {
-      xt0 = __builtin_amdgcn_exp2f(x[r] * kLogitScale);
+      xt0 = __builtin_amdgcn_exp2f(kExact ? x[r] * kLogitScale : x[r]);
       asm volatile("" : "+v"(xt0));
     } else if (st == 1) {
-      xt1 = __builtin_amdgcn_exp2f(x[r + 1] * kLogitScale);
+      xt1 = __builtin_amdgcn_exp2f(kExact ? x[r + 1] * kLogitScale : x[r + 1]);
       asm volatile("" : "+v"(xt1));
     } else {
       // (plain adds for the row sum: they co-issue with MFMAs, dot instructions do not)
@@ -798,25 +799,19 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   }  // work loop
 }
 
-template <int D, int BLK>
+template <int D, int BLK, bool kExact>
 static int launch_attn_t(const heart_shape &s, const void *q, const void *k, const void *v,
                          const int *kept_idx, const int *kept_count, float scale, void *out,
                          float *lse, int *order, hipStream_t st) {
   const int Nb = (s.N + BLK - 1) / BLK;
   const int BH = s.B * s.H;
   const size_t lds = 4 * (size_t)kStageRows * D * 2;  // >= BLK * (D + 8) * 2 of the output staging
-  auto kern = attn_kernel<D, BLK>;
+  auto kern = attn_kernel<D, BLK, kExact>;
   const int dev = current_device();
   if (dev < 0) return fail(HEART_EHIP, "heart_block_sparse_attn: cannot identify the current device");
-  static bool attr_set[kMaxDevices] = {};  // the attribute is per function and device
-  if (!attr_set[dev]) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess)
-      return fail(HEART_EHIP, "hipFuncSetAttribute(max dynamic LDS %zu): %s", lds,
-                  hipGetErrorString(e));
-    attr_set[dev] = true;
-  }
+  static DeviceFlags attr_set;  // per instantiation: the attribute is per function and device
+  if (hipError_t e = set_max_lds_once(attr_set, dev, reinterpret_cast<const void *>(kern), (int)lds))
+    return fail(HEART_EHIP, "hipFuncSetAttribute(max dynamic LDS %zu): %s", lds, hipGetErrorString(e));
   const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
   const float scale_log2e = sc * 1.4426950408889634f;
   const long long n_items = (long long)BH * Nb;
@@ -824,14 +819,9 @@ static int launch_attn_t(const heart_shape &s, const void *q, const void *k, con
   if (order) {
     // persistent workgroups: as many as are resident at once (HEART_ATTN_OCC per SIMD, i.e.
     // two workgroups of four wavefronts per CU)
-    static int n_cu[kMaxDevices] = {};
-    if (n_cu[dev] == 0) {
-      int v = 0;
-      if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
-        return fail(HEART_EHIP, "heart_block_sparse_attn: cannot query the number of CUs");
-      n_cu[dev] = v;
-    }
-    const long long resident = (long long)n_cu[dev] * HEART_ATTN_OCC * 4 / (BLK / 32);
+    const int n_cu = cu_count(dev);
+    if (n_cu <= 0) return fail(HEART_EHIP, "heart_block_sparse_attn: cannot query the number of CUs");
+    const long long resident = (long long)n_cu * HEART_ATTN_OCC * 4 / (BLK / 32);
     grid = n_items < resident ? n_items : resident;
   }
   if (grid > 0x7fffffffLL) return fail(HEART_EUNSUPPORTED, "heart_block_sparse_attn: grid too large");
@@ -839,15 +829,10 @@ static int launch_attn_t(const heart_shape &s, const void *q, const void *k, con
     const uint32_t mult = (uint32_t)(((kOrderClasses - 1) << 16) / Nb);
     if (Nb <= kOrderStagedMax) {
       auto okern = attn_order_kernel<true>;
-      static bool order_attr_set[kMaxDevices] = {};
-      if (!order_attr_set[dev]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(okern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           kOrderStagedMax);
-        if (e != hipSuccess)
-          return fail(HEART_EHIP, "hipFuncSetAttribute(order kernel LDS): %s", hipGetErrorString(e));
-        order_attr_set[dev] = true;
-      }
+      static DeviceFlags order_attr_set;
+      if (hipError_t e = set_max_lds_once(order_attr_set, dev, reinterpret_cast<const void *>(okern),
+                                          kOrderStagedMax))
+        return fail(HEART_EHIP, "hipFuncSetAttribute(order kernel LDS): %s", hipGetErrorString(e));
       hipLaunchKernelGGL(okern, dim3((unsigned)BH), dim3(256), (size_t)((Nb + 15) / 16 * 16), st,
                          kept_count, BH, Nb, mult, order);
     } else {
@@ -867,9 +852,25 @@ static int launch_attn_t(const heart_shape &s, const void *q, const void *k, con
   return check_launch("attn_kernel");
 }
 
+template <bool kExact>
+static int launch_attn_e(const heart_shape &s, const void *q, const void *k, const void *v,
+                         const int *kept_idx, const int *kept_count, float scale, void *out,
+                         float *lse, int *order, hipStream_t st) {
+  if (s.D == 128 && s.block == 128)
+    return launch_attn_t<128, 128, kExact>(s, q, k, v, kept_idx, kept_count, scale, out, lse, order, st);
+  if (s.D == 128 && s.block == 64)
+    return launch_attn_t<128, 64, kExact>(s, q, k, v, kept_idx, kept_count, scale, out, lse, order, st);
+  if (s.D == 64 && s.block == 128)
+    return launch_attn_t<64, 128, kExact>(s, q, k, v, kept_idx, kept_count, scale, out, lse, order, st);
+  if (s.D == 64 && s.block == 64)
+    return launch_attn_t<64, 64, kExact>(s, q, k, v, kept_idx, kept_count, scale, out, lse, order, st);
+  return fail(HEART_EUNSUPPORTED, "heart_block_sparse_attn: unsupported (D, block) = (%d, %d)",
+              s.D, s.block);
+}
+
 int launch_attn(const heart_shape &s, const void *q, const void *k, const void *v,
-                const int *kept_idx, const int *kept_count, float scale, void *out, float *lse,
-                int *order, hipStream_t st) {
+                const int *kept_idx, const int *kept_count, float scale, unsigned flags, void *out,
+                float *lse, int *order, hipStream_t st) {
   // the kernel addresses one head's rows through 32-bit buffer offsets
   const long long lim = 0xffffffffLL;
   const long long rows = (long long)s.N + 2 * s.block;  // staging may address a few rows past N
@@ -878,14 +879,9 @@ int launch_attn(const heart_shape &s, const void *q, const void *k, const void *
     return fail(HEART_EUNSUPPORTED,
                 "heart_block_sparse_attn: (N + 2*block) * token stride * 2 bytes must stay "
                 "below 4 GiB");
-  if (s.D == 128 && s.block == 128)
-    return launch_attn_t<128, 128>(s, q, k, v, kept_idx, kept_count, scale, out, lse, order, st);
-  if (s.D == 64 && s.block == 128)
-    return launch_attn_t<64, 128>(s, q, k, v, kept_idx, kept_count, scale, out, lse, order, st);
-  if (s.D == 64 && s.block == 64)
-    return launch_attn_t<64, 64>(s, q, k, v, kept_idx, kept_count, scale, out, lse, order, st);
-  return fail(HEART_EUNSUPPORTED, "heart_block_sparse_attn: unsupported (D, block) = (%d, %d)",
-              s.D, s.block);
+  if (flags & HEART_ATTN_FOLD_SCALE)
+    return launch_attn_e<false>(s, q, k, v, kept_idx, kept_count, scale, out, lse, order, st);
+  return launch_attn_e<true>(s, q, k, v, kept_idx, kept_count, scale, out, lse, order, st);
 }
 
 }  // namespace heart

@@ -117,12 +117,14 @@ int heart_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float 
                           (hipStream_t)stream);
 }
 
-int heart_block_sparse_attn(const heart_shape *shape, const void *q, const void *k,
-                            const void *v, const int *kept_idx, const int *kept_count,
-                            float scale, void *out, float *lse, void *workspace,
-                            size_t workspace_bytes, void *stream) {
+static int attn_checked(const heart_shape *shape, const void *q, const void *k, const void *v,
+                        const int *kept_idx, const int *kept_count, float scale, unsigned flags,
+                        void *out, float *lse, void *workspace, size_t workspace_bytes,
+                        void *stream) {
   clear_error();
   if (int rc = check_shape(shape, "heart_block_sparse_attn")) return rc;
+  if (flags & ~HEART_ATTN_FOLD_SCALE)
+    return fail(HEART_EINVAL, "heart_block_sparse_attn: unknown flag bits 0x%x", flags);
   if (!q || !k || !v || !kept_idx || !kept_count || !out)
     return fail(HEART_EINVAL, "heart_block_sparse_attn: NULL pointer argument");
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
@@ -133,10 +135,6 @@ int heart_block_sparse_attn(const heart_shape *shape, const void *q, const void 
     return fail(HEART_EUNSUPPORTED,
                 "heart_block_sparse_attn: strides must be multiples of 8 elements, token "
                 "stride > 0");
-  if (shape->block == 64 && shape->D != 64)
-    return fail(HEART_EUNSUPPORTED,
-                "heart_block_sparse_attn: supported (D, block) pairs are (128,128), (64,128), "
-                "(64,64)");
   if (workspace) {
     if (!aligned16(workspace))
       return fail(HEART_EUNSUPPORTED, "heart_block_sparse_attn: workspace must be 16-byte aligned");
@@ -144,15 +142,37 @@ int heart_block_sparse_attn(const heart_shape *shape, const void *q, const void 
       return fail(HEART_EINVAL, "heart_block_sparse_attn: workspace of %zu bytes, need %zu",
                   workspace_bytes, heart_attn_workspace_bytes(shape));
   }
-  return launch_attn(*shape, q, k, v, kept_idx, kept_count, scale, out, lse, (int *)workspace,
-                     (hipStream_t)stream);
+  return launch_attn(*shape, q, k, v, kept_idx, kept_count, scale, flags, out, lse,
+                     (int *)workspace, (hipStream_t)stream);
+}
+
+int heart_block_sparse_attn(const heart_shape *shape, const void *q, const void *k,
+                            const void *v, const int *kept_idx, const int *kept_count,
+                            float scale, void *out, float *lse, void *workspace,
+                            size_t workspace_bytes, void *stream) {
+  return attn_checked(shape, q, k, v, kept_idx, kept_count, scale, 0u, out, lse, workspace,
+                      workspace_bytes, stream);
+}
+
+int heart_block_sparse_attn_flags(const heart_shape *shape, const void *q, const void *k,
+                                  const void *v, const int *kept_idx, const int *kept_count,
+                                  float scale, unsigned flags, void *out, float *lse,
+                                  void *workspace, size_t workspace_bytes, void *stream) {
+  return attn_checked(shape, q, k, v, kept_idx, kept_count, scale, flags, out, lse, workspace,
+                      workspace_bytes, stream);
+}
+
+size_t heart_workspace_bytes(int B, int H, int Nb, int D) {
+  (void)D;
+  if (B <= 0 || H <= 0 || Nb <= 0) return 0;
+  // plan header (24 ints) + two entries per head + one entry per (head, query block)
+  return ((size_t)B * H * ((size_t)Nb + 2) + 24) * sizeof(int);
 }
 
 size_t heart_attn_workspace_bytes(const heart_shape *s) {
   if (!s || s->B <= 0 || s->H <= 0 || s->N <= 0 || s->block <= 0) return 0;
-  const size_t nb = ((size_t)s->N + s->block - 1) / s->block;
-  // plan header (24 ints) + two entries per head + one entry per (head, query block)
-  return ((size_t)s->B * s->H * (nb + 2) + 24) * sizeof(int);
+  const long long nb = ((long long)s->N + s->block - 1) / s->block;
+  return heart_workspace_bytes(s->B, s->H, (int)nb, s->D);
 }
 
 static int check_antidiag(const heart_shape *s, int stride, const char *fn) {
@@ -245,6 +265,15 @@ int heart_ubench_mfma_bf16(const void *a_bf16, const void *b_bf16, int n_workgro
   if (n_workgroups <= 0 || iters <= 0 || n_workgroups > (1 << 20) || iters > (1 << 24))
     return fail(HEART_EINVAL, "heart_ubench_mfma_bf16: n_workgroups in [1, 2^20], iters in [1, 2^24]");
   return launch_ubench_mfma(a_bf16, b_bf16, n_workgroups, iters, sink, (hipStream_t)stream);
+}
+
+int heart_ubench_read(const void *src, size_t bytes, unsigned *sink, void *stream) {
+  clear_error();
+  if (!src || !sink) return fail(HEART_EINVAL, "heart_ubench_read: NULL pointer argument");
+  if (!aligned16(src) || bytes % 16 != 0 || bytes == 0)
+    return fail(HEART_EUNSUPPORTED,
+                "heart_ubench_read: src 16-byte aligned, bytes a positive multiple of 16");
+  return launch_ubench_read(src, bytes, sink, (hipStream_t)stream);
 }
 
 int heart_ubench_copy(const void *src, void *dst, size_t bytes, void *stream) {

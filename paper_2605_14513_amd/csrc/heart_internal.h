@@ -4,7 +4,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "heart.h"
+#include "heart_diag.h"
 
 namespace heart {
 
@@ -158,6 +161,29 @@ inline int current_device() {
   return dev;
 }
 
+// Per-device "done" flags for set-up that is per function and device (launch attributes,
+// device queries).  Host threads may race on the first call: the set-up calls are
+// idempotent and the flags are atomic, so the worst case is that two threads both do it.
+struct DeviceFlags {
+  std::atomic<int> v[kMaxDevices];
+};
+inline hipError_t set_max_lds_once(DeviceFlags &f, int dev, const void *kern, int bytes) {
+  if (f.v[dev].load(std::memory_order_acquire)) return hipSuccess;
+  const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) f.v[dev].store(1, std::memory_order_release);
+  return e;
+}
+// Number of compute units of device `dev` (0 on error), queried once per device.
+inline int cu_count(int dev) {
+  static DeviceFlags n;
+  int v = n.v[dev].load(std::memory_order_acquire);
+  if (v > 0) return v;
+  if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+    return 0;
+  n.v[dev].store(v, std::memory_order_release);
+  return v;
+}
+
 // launchers implemented per kernel file
 int launch_pool(const heart_shape &s, const void *q, const void *k, float *qblk, float *kblk,
                 float *qmean, float *kmean, hipStream_t st);
@@ -170,8 +196,8 @@ int launch_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float
                      int n_always_kv, int n_dense_q, int min_keep, unsigned char *mask,
                      int *kept_idx, int *kept_count, float *scores_out, hipStream_t st);
 int launch_attn(const heart_shape &s, const void *q, const void *k, const void *v,
-                const int *kept_idx, const int *kept_count, float scale, void *out, float *lse,
-                int *order, hipStream_t st);
+                const int *kept_idx, const int *kept_count, float scale, unsigned flags, void *out,
+                float *lse, int *order, hipStream_t st);
 
 int launch_antidiag(const heart_shape &s, const void *q, const void *k, int stride,
                     const unsigned char *refresh, float *scores, float *workspace, hipStream_t st);
@@ -186,5 +212,6 @@ int ebc_select_host(int n, int k, const double *E, const double *S, double s_min
 int launch_ubench_mfma(const void *a, const void *b, int n_wg, int iters, float *sink,
                        hipStream_t st);
 int launch_ubench_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
+int launch_ubench_read(const void *src, size_t bytes, unsigned *sink, hipStream_t st);
 
 }  // namespace heart

@@ -329,7 +329,9 @@ __global__ __launch_bounds__(64 * kWaves) void mask_topp_kernel(
 #pragma unroll
     for (int c = 0; c < CMAX; ++c) {
       int j = lane + 64 * c;
-      float pc = (j < Nb && p[c] > 0.f) ? p[c] : 0.f;
+      // (scores handed in may be anything: negative values and NaN count as 0, values above
+      // 1 as 1, so the fixed-point conversion below cannot overflow)
+      float pc = (j < Nb && p[c] > 0.f) ? fminf(p[c], 1.0f) : 0.f;
       e[c] = __float_as_uint(pc);
       u[c] = (uint32_t)floorf(pc * 1073741824.0f);  // exact: power-of-two scaling
       my_u += u[c];
@@ -445,14 +447,10 @@ static int launch_cmax(int B, int H, int Nb, int D, const float *qblk, const flo
   if (lds > 64 * 1024) {
     const int dev = current_device();
     if (dev < 0) return fail(HEART_EHIP, "heart_mask_topp: cannot identify the current device");
-    static bool attr_set[kMaxDevices] = {};  // per instantiation: the attribute is per function and device
-    if (!attr_set[dev]) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(mask_topp_kernel<CMAX>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-      if (e != hipSuccess)
-        return fail(HEART_EHIP, "hipFuncSetAttribute(mask kernel LDS): %s", hipGetErrorString(e));
-      attr_set[dev] = true;
-    }
+    static DeviceFlags attr_set;  // per instantiation: the attribute is per function and device
+    if (hipError_t e = set_max_lds_once(attr_set, dev, reinterpret_cast<const void *>(mask_topp_kernel<CMAX>),
+                                        96 * 1024))
+      return fail(HEART_EHIP, "hipFuncSetAttribute(mask kernel LDS): %s", hipGetErrorString(e));
   }
   hipLaunchKernelGGL(mask_topp_kernel<CMAX>, dim3((unsigned)nwg), dim3(64 * kWaves), lds, st, H, Nb, D,
                      qblk, kblk, scores_in, tau, refresh, n_always_kv, n_dense_q, min_keep, mask,

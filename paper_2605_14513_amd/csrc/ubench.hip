@@ -1,5 +1,6 @@
 // Diagnostic kernels that measure what the chip sustains, for the roofline accounting of
-// the benchmark: the bf16 matrix-core rate on given operand data, and a plain copy.
+// the benchmark: the bf16 matrix-core rate on given operand data, a plain copy, and a
+// read-only stream with the access pattern of the pooling kernel.
 // MI355X is power limited: the sustained clock, and with it the matrix-core rate,
 // depends on the bits that flow through the MFMA units (all-zero operands run at the
 // nominal clock, normally distributed ones about 30 % slower), so the attainable
@@ -52,6 +53,34 @@ __global__ __launch_bounds__(256) void ubench_copy_kernel(const ub_u32x4_t *__re
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
     dst[i] = __builtin_nontemporal_load(src + i);
+}
+
+// One workgroup per 32 KB: every lane issues its eight 16-byte non-temporal loads before it
+// uses any (the pooling kernel's pattern), then folds them into one word.
+__global__ __launch_bounds__(256) void ubench_read_kernel(const ub_u32x4_t *__restrict__ src,
+                                                          size_t n16, unsigned *sink) {
+  const size_t base = (size_t)blockIdx.x * 2048 + threadIdx.x;
+  ub_u32x4_t v[8];
+#pragma unroll
+  for (int p = 0; p < 8; ++p) {
+    const size_t i = base + (size_t)p * 256;
+    v[p] = ub_u32x4_t{0u, 0u, 0u, 0u};
+    if (i < n16) v[p] = __builtin_nontemporal_load(src + i);
+  }
+  unsigned x = 0;
+#pragma unroll
+  for (int p = 0; p < 8; ++p) x ^= v[p].x ^ v[p].y ^ v[p].z ^ v[p].w;
+  // keeps the loads alive; the comparison is practically never true
+  if (x == 0x9e3779b9u && threadIdx.x == 255u) sink[0] = x;
+}
+
+int launch_ubench_read(const void *src, size_t bytes, unsigned *sink, hipStream_t st) {
+  const size_t n16 = bytes / 16;
+  const size_t nwg = (n16 + 2047) / 2048;
+  if (nwg > 0x7fffffffULL) return fail(HEART_EUNSUPPORTED, "heart_ubench_read: too many bytes");
+  hipLaunchKernelGGL(ubench_read_kernel, dim3((unsigned)nwg), dim3(256), 0, st,
+                     (const ub_u32x4_t *)src, n16, sink);
+  return check_launch("ubench_read_kernel");
 }
 
 int launch_ubench_mfma(const void *a, const void *b, int n_wg, int iters, float *sink,

@@ -1,7 +1,9 @@
-"""Helpers shared by the GPU parity tests (no method arithmetic here)."""
+"""Helpers shared by the GPU parity tests (no method arithmetic here: every expected value
+comes from the `oracle` package)."""
 import numpy as np
 import torch
 
+import oracle
 from heart_synth import as_u16
 
 SCORE_RTOL = 1e-5          # spec tolerance on block scores (relative)
@@ -100,9 +102,42 @@ def check_attn_plan(ws, cnt, Nb):
         assert np.array_equal(seq[h * Nb:(h + 1) * Nb], want), f"items of head {h}"
 
 
-def assert_masks_equal_up_to_threshold(gmask, omask, osc, ocnt, tau, what: str, tol: float = 1e-4):
+def attn_atol(want: np.ndarray) -> float:
+    """Bound on |out - exact| for bf16 outputs: the 2e-2 of unit-scale outputs, growing with the
+    output's magnitude beyond 2 (an output of magnitude m is rounded to bf16 with an error of up
+    to 2^-9 m, and the rounded softmax weights contribute as much again)."""
+    return ATTN_ATOL * max(1.0, float(np.nanmax(np.abs(want))) / 2.0)
+
+
+def sample_query_blocks(rng, Nb: int, n_text_blocks: int, n: int = 32):
+    """At least n query blocks (all of them when Nb <= n): block 0, the (possibly ragged) last
+    block, the text blocks, and seeded random ones."""
+    fixed = sorted(set([0, Nb - 1] + list(range(min(n_text_blocks, Nb)))))
+    if Nb <= n:
+        return list(range(Nb))
+    rest = [i for i in rng.permutation(Nb).tolist() if i not in fixed]
+    return sorted(fixed + rest[:n - len(fixed)])
+
+
+def pooled_mean_score_shift(osc: np.ndarray, qblk_gpu, kblk_gpu) -> np.ndarray:
+    """How far the GPU's own block means (equal to the oracle's within the pooling tolerance)
+    can move the scores of a row: the largest relative change, per row [B,H,Nb], between the
+    oracle's scores on the oracle's block means (osc) and the oracle's scores on the GPU's."""
+    osc2 = oracle.scores(qblk_gpu.detach().cpu().numpy(), kblk_gpu.detach().cpu().numpy())
+    big = osc >= SCORE_QUANTUM
+    rel = np.where(big, np.abs(osc2.astype(np.float64) - osc) / np.where(big, osc, 1.0), 0.0)
+    return rel.max(-1)
+
+
+def assert_masks_equal_up_to_threshold(gmask, omask, osc, ocnt, tau, what: str,
+                                       tol: float = SCORE_RTOL, row_tol=None):
     """GPU-chained masks may differ from the oracle's only in rows whose cumulative mass passes
-    within the score tolerance of the threshold.  Returns the boolean [B,H,Nb] 'row is equal'."""
+    within the score tolerance of the threshold: every score agrees within `tol` relative, so
+    a normalised cumulative mass (a sum of scores) moves by at most `tol`.  `row_tol` [B,H,Nb]
+    adds what the caller has measured on the oracle's side for inputs that are themselves only
+    equal within a tolerance (pooled_mean_score_shift).  Returns the boolean [B,H,Nb] 'row is
+    equal'."""
+    gmask = gmask.cpu().numpy() if isinstance(gmask, torch.Tensor) else gmask
     B, H, Nb, _ = omask.shape
     diff = (gmask != omask).any(-1)
     for (b, h, i) in np.argwhere(diff):
@@ -110,7 +145,38 @@ def assert_masks_equal_up_to_threshold(gmask, omask, osc, ocnt, tau, what: str, 
         order = np.argsort(-p, kind="stable")
         cum = np.cumsum(p[order]) / p.sum()
         kk = min(int(ocnt[b, h, i]), Nb) - 1
-        assert abs(cum[kk] - tau[h]) < tol or abs(cum[max(kk - 1, 0)] - tau[h]) < tol, \
-            f"{what}: mask row {(b, h, i)} differs away from the threshold"
+        t = tol + (0.0 if row_tol is None else float(row_tol[b, h, i]))
+        assert abs(cum[kk] - tau[h]) < t or abs(cum[max(kk - 1, 0)] - tau[h]) < t, \
+            (f"{what}: mask row {(b, h, i)} differs away from the threshold "
+             f"(mass {cum[kk]:.7f} / {cum[max(kk - 1, 0)]:.7f}, tau {tau[h]:.7f}, tolerance {t:.1e})")
     assert diff.sum() <= max(1, 0.01 * B * H * Nb), f"{what}: {diff.sum()} rows differ"
     return ~diff
+
+
+class OracleChain:
+    """The oracle's side of a chained run: caller-owned TMR state (anchors, cached mask and
+    lists) carried from step to step through the oracle's single-step functions, in the order
+    of Alg. 1."""
+
+    def __init__(self, cfg, tau, delta, gate=(0.4, 0.8)):
+        B, H, D, Nb = cfg.B, cfg.H, cfg.D, cfg.Nb
+        self.cfg, self.tau, self.delta, self.gate = cfg, tau, delta, gate
+        self.qa = np.zeros((B, H, D), np.float32)
+        self.ka = np.zeros((B, H, D), np.float32)
+        self.has = np.zeros((B, H), np.uint8)
+        self.mask = np.zeros((B, H, Nb, Nb), np.uint8)
+        self.idx = np.zeros((B, H, Nb, Nb), np.int32)
+        self.cnt = np.zeros((B, H, Nb), np.int32)
+
+    def step(self, st):
+        """st: StepInputs (CPU bf16).  Returns drift, refresh and the scores of this step; mask,
+        idx, cnt are updated in place for refreshed heads."""
+        cfg = self.cfg
+        nt = cfg.n_text_blocks
+        self.qblk, qm = oracle.pool(u16(st.q), cfg.block)
+        self.kblk, km = oracle.pool(u16(st.k), cfg.block)
+        d, r = oracle.drift(qm, km, self.qa, self.ka, self.has, self.delta, *self.gate)
+        self.scores = oracle.scores(self.qblk, self.kblk)
+        oracle.topp(self.scores, self.tau, refresh=r, n_always_kv=nt, n_dense_q=nt, mask=self.mask,
+                    kept_idx=self.idx, kept_count=self.cnt)
+        return d, r

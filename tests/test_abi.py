@@ -1,6 +1,6 @@
 """CPU-side checks of the boundary: the library builds, loads and exports every
-symbol that include/heart.h declares, and host-side validation rejects bad calls
-before anything touches a GPU."""
+symbol that include/heart.h and include/heart_diag.h declare, and host-side validation
+rejects bad calls before anything touches a GPU."""
 import ctypes
 import os
 import re
@@ -20,17 +20,23 @@ def lib():
     return binding.load_library()
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "heart.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(heart_[a-z_0-9]+)\s*\(", text)))
+def declared_symbols(headers=("heart.h", "heart_diag.h")):
+    syms = set()
+    for h in headers:
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        syms |= set(re.findall(r"\b(heart_[a-z_0-9]+)\s*\(", text))
+    return sorted(syms)
 
 
 def test_header_declares_the_four_hot_path_calls():
-    syms = declared_symbols()
+    syms = declared_symbols(("heart.h",))
     for s in ("heart_pool_qk", "heart_drift", "heart_mask_topp", "heart_block_sparse_attn",
-              "heart_last_error", "heart_version"):
+              "heart_workspace_bytes", "heart_last_error", "heart_version"):
         assert s in syms
+    # diagnostics live in their own header
+    assert not [s for s in syms if "ubench" in s]
+    assert "heart_ubench_read" in declared_symbols(("heart_diag.h",))
 
 
 def test_library_exports_every_declared_symbol(lib):
@@ -71,6 +77,16 @@ def test_host_validation_rejects_bad_calls_without_a_gpu(lib):
     s.block = 128
     assert lib.heart_attn_workspace_bytes(ctypes.byref(s)) == (1 * 2 * (1 + 2) + 24) * 4
     assert lib.heart_attn_workspace_bytes(None) == 0
+    assert lib.heart_workspace_bytes(1, 2, 1, 128) == (1 * 2 * (1 + 2) + 24) * 4
+    assert lib.heart_workspace_bytes(1, 40, 256, 128) == (40 * 258 + 24) * 4
+    assert lib.heart_workspace_bytes(0, 2, 1, 128) == 0
+    fake = ctypes.c_void_p(0x10000)
+    for arr in (s.q_stride, s.k_stride, s.v_stride, s.o_stride):
+        arr[0], arr[1], arr[2] = 2 * 100 * 128, 100 * 128, 128
+    # unknown option bits are refused before anything is launched
+    assert lib.heart_block_sparse_attn_flags(ctypes.byref(s), fake, fake, fake, fake, fake, 0.0, 2,
+                                             fake, None, None, 0, None) == -1
+    assert b"flag" in lib.heart_last_error()
     assert lib.heart_drift(1, 2, 96, None, None, None, None, None, None, 0.4, 0.8, 1, None, None,
                            None) == -2
     assert lib.heart_drift(1, 2, 64, None, None, None, None, None, None, 0.4, 0.8, 1, None, None,

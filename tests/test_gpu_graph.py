@@ -4,13 +4,19 @@ The library promises that a call only enqueues kernels on the given stream: no a
 synchronisation, no memset nodes, no host-side state that changes between calls.  Capturing a
 step (including the attention launch plan, whose list cursors a kernel resets on every
 launch) and replaying it several times, with eager work and synchronisations in between, must
-give the eager results bit for bit on every replay."""
+give the eager results bit for bit on every replay -- and every replay is also checked against
+the oracle's chained run of the same schedule (decisions exact, masks equal up to threshold
+rows, attention within tolerance), so the captured path is held to the same parity bar as the
+eager one."""
 import numpy as np
 import pytest
 import torch
 
+import oracle
+from oracle import antidiag_oracle
 from heart_synth import make_generator
-from heart_testlib import gpu, np_gpu
+from heart_testlib import (ATTN_ATOL, SCORE_RTOL, OracleChain, assert_masks_equal_up_to_threshold, gpu,
+                           np_gpu, pooled_mean_score_shift, u16)
 
 pytestmark = pytest.mark.gpu
 
@@ -95,6 +101,7 @@ def test_captured_step_replays_bit_exact(estimator):
         step(cap)
     # the capture itself does not execute: state is still the reset one
     assert not cap["has"].any().item()
+    chain = OracleChain(cfg, g.tau, g.delta)
     for rep, st in enumerate(steps):
         load(cap, st)                      # eager work between replays
         torch.cuda.synchronize()
@@ -102,6 +109,36 @@ def test_captured_step_replays_bit_exact(estimator):
         torch.cuda.synchronize()
         for key, ref in want[rep].items():
             assert torch.equal(cap[key], ref), f"replay {rep}: {key} differs from the eager run"
+        # the same replay against the oracle's chain
+        od, orf = chain.step(st)
+        assert np.array_equal(cap["refresh"].cpu().numpy(), orf), f"replay {rep}: decisions differ from the oracle"
+        assert np.array_equal(cap["has"].cpu().numpy(), chain.has)
+        fin = np.isfinite(od)
+        assert np.allclose(cap["drift"].cpu().numpy()[fin], od[fin], rtol=1e-4, atol=1e-6)
+        if estimator == "pooled":
+            osc, tol = chain.scores, SCORE_RTOL
+            shift = pooled_mean_score_shift(osc, cap["qblk"], cap["kblk"])
+        else:
+            # the oracle's lists for this estimator: its own scores, the same top-p rule and cache
+            osc = np.stack([np.stack([antidiag_oracle.antidiag_scores(
+                st.q[b, h].double().numpy(), st.k[b, h].double().numpy(), blk, blk // 8)
+                for h in range(H)]) for b in range(B)]).astype(np.float32)
+            if rep == 0:
+                amask, aidx, acnt = (np.zeros_like(chain.mask), np.zeros_like(chain.idx), np.zeros_like(chain.cnt))
+            oracle.topp(osc, g.tau, refresh=orf, n_always_kv=nt, n_dense_q=nt, mask=amask, kept_idx=aidx,
+                        kept_count=acnt)
+            chain.mask, chain.idx, chain.cnt = amask, aidx, acnt
+            tol, shift = 2e-3, None  # score tolerance of the antidiagonal-style estimator
+        gm = cap["mask"].cpu().numpy()
+        fresh = orf.astype(bool)[:, :, None, None]
+        assert_masks_equal_up_to_threshold(np.where(fresh, gm, chain.mask), chain.mask, osc, chain.cnt, g.tau,
+                                           f"{estimator} replay {rep}", tol=tol, row_tol=shift)
+        same = ~(gm != chain.mask).any(-1)
+        assert np.array_equal(cap["kcnt"].cpu().numpy()[same], chain.cnt[same])
+        oout = oracle.attn(u16(st.q), u16(st.k), u16(st.v), blk, chain.idx, chain.cnt)
+        rows_same = np.repeat(same, blk, axis=2)[:, :, :N]
+        err = np.abs(cap["out"].float().cpu().numpy().astype(np.float64) - oout)[rows_same].max()
+        assert err <= ATTN_ATOL, f"replay {rep}: attention max abs err {err:.4f} against the oracle"
     # and once more from a fresh cache: the same graph, replayed after a reset
     for key in ("qa", "ka", "has"):
         cap[key].zero_()

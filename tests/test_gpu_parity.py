@@ -8,9 +8,11 @@ its own intermediates):
   P2 drift  fed oracle means          drift, refresh, anchors bit-equal
   P3 scores fed oracle block means    within 1e-5 relative
   P4 top-p  fed oracle scores         mask / kept_idx / kept_count bit-equal
-  P5 attn   fed oracle kept lists     max-abs <= 2e-2
+  P5 attn   fed oracle kept lists     max-abs <= 2e-2 (times max|out|/2 where outputs exceed 2)
   P6 chain  pool->drift->mask->attn   tolerances as above; mask rows that differ must
-                                      be threshold ties within the score tolerance
+                                      be threshold ties within the score tolerance (1e-5 on
+                                      the normalised cumulative mass, plus what the GPU's own
+                                      block means move the oracle's scores)
 """
 import numpy as np
 import pytest
@@ -18,8 +20,9 @@ import torch
 
 import oracle
 from heart_synth import make_generator
-from heart_testlib import (check_attn_plan, ATTN_ATOL, assert_lists_equal, assert_means_close,
-                           assert_scores_close, gpu, np_gpu, u16)
+from heart_testlib import (ATTN_ATOL, OracleChain, assert_lists_equal, assert_masks_equal_up_to_threshold,
+                           assert_means_close, assert_scores_close, attn_atol, check_attn_plan, gpu,
+                           np_gpu, pooled_mean_score_shift, u16)
 
 pytestmark = pytest.mark.gpu
 
@@ -391,17 +394,13 @@ def test_chained_steps_match_oracle(heart, name):
     cfg = g.cfg
     B, H, D, Nb, nt = cfg.B, cfg.H, cfg.D, cfg.Nb, cfg.n_text_blocks
     dev = "cuda"
-    # caller-owned state, GPU and oracle copies
+    # caller-owned state: the GPU's, and the oracle's inside OracleChain
     gq = torch.zeros((B, H, D), device=dev); gk = torch.zeros((B, H, D), device=dev)
     gh = torch.zeros((B, H), dtype=torch.uint8, device=dev)
     gmask = torch.zeros((B, H, Nb, Nb), dtype=torch.uint8, device=dev)
     gidx = torch.zeros((B, H, Nb, Nb), dtype=torch.int32, device=dev)
     gcnt = torch.zeros((B, H, Nb), dtype=torch.int32, device=dev)
-    gscores = torch.zeros((B, H, Nb, Nb), dtype=torch.float32, device=dev)
-    oq = np.zeros((B, H, D), np.float32); ok_ = np.zeros((B, H, D), np.float32)
-    oh = np.zeros((B, H), np.uint8)
-    omask = np.zeros((B, H, Nb, Nb), np.uint8); oidx = np.zeros((B, H, Nb, Nb), np.int32)
-    ocnt = np.zeros((B, H, Nb), np.int32)
+    chain = OracleChain(cfg, g.tau, g.delta)
     gtau, gdelta = np_gpu(g.tau), np_gpu(g.delta)
     for s in range(cfg.steps):
         _, st = case(name, s)
@@ -410,64 +409,81 @@ def test_chained_steps_match_oracle(heart, name):
         qblk, kblk, qmean, kmean = heart.heart_pool_qk(q, k, cfg.block)
         d, r = heart.heart_drift(qmean, kmean, gq, gk, gh, gdelta, 0.4, 0.8)
         heart.heart_mask_topp(qblk, kblk, gtau, refresh=r, n_always_kv_blocks=nt,
-                              n_dense_q_blocks=nt, mask=gmask, kept_idx=gidx, kept_count=gcnt,
-                              scores_out=gscores)
+                              n_dense_q_blocks=nt, mask=gmask, kept_idx=gidx, kept_count=gcnt)
         out = heart.heart_block_sparse_attn(q, k, v, cfg.block, gidx, gcnt)
         torch.cuda.synchronize()
-        # oracle step
-        oqb, oqm = oracle.pool(u16(st.q), cfg.block)
-        okb, okm = oracle.pool(u16(st.k), cfg.block)
-        od, orf = oracle.drift(oqm, okm, oq, ok_, oh, g.delta, 0.4, 0.8)
-        osc = oracle.scores(oqb, okb)
-        oracle.topp(osc, g.tau, refresh=orf, n_always_kv=nt, n_dense_q=nt, mask=omask,
-                    kept_idx=oidx, kept_count=ocnt)
-        oout = oracle.attn(u16(st.q), u16(st.k), u16(st.v), cfg.block, oidx, ocnt)
+        od, orf = chain.step(st)
+        oout = oracle.attn(u16(st.q), u16(st.k), u16(st.v), cfg.block, chain.idx, chain.cnt)
         # decisions: a GPU/oracle disagreement is only legitimate if the drift sits
         # within rounding of delta; the synthetic schedules keep clear of it
         assert np.array_equal(r.cpu().numpy(), orf), f"step {s}: refresh decisions differ"
         gd = d.cpu().numpy()
         fin = np.isfinite(od)
         assert np.allclose(gd[fin], od[fin], rtol=1e-4, atol=1e-6)
-        # masks: rows may differ only where the cumulative mass passes within the score
-        # tolerance of the threshold
+        # masks of the heads refreshed at this step: rows may differ only where the cumulative
+        # mass passes within the score tolerance of the threshold (reused heads keep masks that
+        # were checked at the step that made them)
+        shift = pooled_mean_score_shift(chain.scores, qblk, kblk)
+        fresh = orf.astype(bool)[:, :, None]
         gm = gmask.cpu().numpy()
-        diff_rows = np.argwhere((gm != omask).any(-1))
-        for (b, h, i) in diff_rows:
-            p = osc[b, h, i].astype(np.float64)
-            order = np.argsort(-p, kind="stable")
-            cum = np.cumsum(p[order]) / p.sum()
-            kk = min(int(ocnt[b, h, i]), Nb) - 1
-            assert abs(cum[kk] - g.tau[h]) < 1e-4 or abs(cum[max(kk - 1, 0)] - g.tau[h]) < 1e-4, \
-                f"step {s}: mask row {(b, h, i)} differs away from the threshold"
-        assert len(diff_rows) <= max(1, 0.01 * B * H * Nb)
-        same = ~(gm != omask).any(-1)
+        assert_masks_equal_up_to_threshold(
+            np.where(fresh[..., None], gm, chain.mask), chain.mask, chain.scores, chain.cnt, g.tau,
+            f"{name} step {s}", row_tol=shift)
+        same = ~(gm != chain.mask).any(-1)
         got = out.float().cpu().numpy().astype(np.float64)
         rows_same = np.repeat(same, cfg.block, axis=2)[:, :, :cfg.N]
         err = np.abs(got - oout)[rows_same].max()
-        assert err <= ATTN_ATOL, f"step {s}: attention max abs err {err:.4f}"
+        assert err <= attn_atol(oout), f"step {s}: attention max abs err {err:.4f}"
 
 
-# ------------------------------------------------------------------------------ shapes
-@pytest.mark.parametrize("amp", [0.5, 1.0, 2.0])
-def test_attn_error_against_input_magnitude(heart, amp):
-    """Precision contract of the attention kernel: Q is multiplied by scale * log2(e) and rounded
-    to bf16 once, i.e. every logit carries the error of one more bf16 rounding of the query
-    (relative 2^-9 per element).  On iid N(0, amp^2) inputs the logits have standard deviation
-    amp^2 and the values amp, so the output error grows like amp^3: inside the 2e-2 budget at
-    amp <= 1 (logits of a few units, what normalised q and k give), about 8 x that at amp = 2
-    (logits of +-12, nearly one-hot rows)."""
+# ------------------------------------------------------------------------------ precision
+@pytest.mark.parametrize("amp", [0.5, 1.0, 2.0, 3.0])
+@pytest.mark.parametrize("fold", [False, True])
+def test_attn_error_against_input_magnitude(heart, amp, fold):
+    """Precision contract of the attention kernel on iid N(0, amp^2) inputs (logits of standard
+    deviation amp^2: +-27 at amp = 3, nearly one-hot rows; outputs of magnitude up to ~4 amp).
+    Default path: logits scaled in fp32, so the error is the bf16 rounding of the weights and of
+    the output and the bound follows the output's magnitude, 2e-2 * max(1, max|out| / 2), at
+    every amplitude.  With HEART_ATTN_FOLD_SCALE the query carries one more bf16 rounding, whose
+    effect grows with the cube of the input scale: the same bound is required up to amp = 2
+    (logits of +-12) and at amp = 3 the path is only required to stay finite and within its
+    documented cube law."""
     B, H, N, D, blk = 1, 2, 700, 128, 128
     Nb = (N + blk - 1) // blk
     gen = torch.Generator().manual_seed(int(amp * 10))
     q, k, v = ((amp * torch.randn((B, H, N, D), generator=gen)).bfloat16() for _ in range(3))
     idx = np.broadcast_to(np.arange(Nb, dtype=np.int32), (B, H, Nb, Nb)).copy()
     cnt = np.full((B, H, Nb), Nb, np.int32)
-    out = heart.heart_block_sparse_attn(gpu(q), gpu(k), gpu(v), blk, np_gpu(idx), np_gpu(cnt))
+    flags = heart.HEART_ATTN_FOLD_SCALE if fold else 0
+    out = heart.heart_block_sparse_attn(gpu(q), gpu(k), gpu(v), blk, np_gpu(idx), np_gpu(cnt), flags=flags)
     torch.cuda.synchronize()
     want = oracle.attn(u16(q), u16(k), u16(v), blk, idx, cnt)
+    got = out.float().cpu().numpy().astype(np.float64)
+    err = np.abs(got - want).max()
+    bound = attn_atol(want)
+    print(f"amp {amp} fold={fold}: max abs err {err:.4f}, bound {bound:.4f} "
+          f"(outputs up to {np.abs(want).max():.1f})", flush=True)
+    if fold and amp > 2.0:
+        assert np.isfinite(got).all() and err <= ATTN_ATOL * amp ** 3
+    else:
+        assert err <= bound
+
+
+@pytest.mark.parametrize("fold", [False, True])
+def test_attn_both_scale_paths_on_the_synthetic_fields(heart, fold):
+    # the workloads' own value range (logits spanning ~8): both paths inside the plain 2e-2
+    g, st = case("small_ragged")
+    cfg = g.cfg
+    qblk, _ = oracle.pool(u16(st.q), cfg.block)
+    kblk, _ = oracle.pool(u16(st.k), cfg.block)
+    _, oi, oc = oracle.topp(oracle.scores(qblk, kblk), g.tau)
+    want = oracle.attn(u16(st.q), u16(st.k), u16(st.v), cfg.block, oi, oc)
+    out = heart.heart_block_sparse_attn(gpu(st.q), gpu(st.k), gpu(st.v), cfg.block, np_gpu(oi), np_gpu(oc),
+                                        flags=heart.HEART_ATTN_FOLD_SCALE if fold else 0)
+    torch.cuda.synchronize()
     err = np.abs(out.float().cpu().numpy().astype(np.float64) - want).max()
-    print(f"amp {amp}: max abs err {err:.4f} (outputs up to {np.abs(want).max():.1f})", flush=True)
-    assert err <= ATTN_ATOL * max(1.0, amp ** 3)
+    print(f"fold={fold}: max abs err {err:.4f}", flush=True)
+    assert err <= ATTN_ATOL
 
 
 @pytest.mark.parametrize("B,H,N,D,blk", [
@@ -478,6 +494,8 @@ def test_attn_error_against_input_magnitude(heart, amp):
     (1, 5, 700, 128, 128),    # fewer heads than XCDs
     (1, 9, 330, 64, 64),      # more heads than XCDs, uneven lists
     (1, 2, 4100, 64, 128),    # 33 blocks, last one with 4 tokens
+    (1, 3, 333, 128, 64),     # D = 128 with blocks of 64 tokens, ragged last block
+    (2, 2, 64, 128, 64),      # the same pair, exactly one block
 ])
 def test_attn_small_and_odd_shapes(heart, B, H, N, D, blk):
     # random bf16 tensors, random kept lists with duplicates and out-of-order entries;

@@ -7,7 +7,7 @@ import torch
 
 import oracle
 from oracle import antidiag_oracle as ao
-from heart_testlib import ATTN_ATOL, assert_means_close, np_gpu, u16
+from heart_testlib import ATTN_ATOL, assert_means_close, attn_atol, np_gpu, u16
 
 pytestmark = pytest.mark.gpu
 
@@ -26,10 +26,10 @@ def heart():
 def test_attention_random_cases(heart, seed):
     rng = np.random.default_rng(seed)
     for case in range(24):
-        D, blk = [(128, 128), (64, 128), (64, 64)][rng.integers(0, 3)]
+        D, blk = [(128, 128), (64, 128), (64, 64), (128, 64)][rng.integers(0, 4)]
         B, H, N = int(rng.integers(1, 3)), int(rng.integers(1, 12)), int(rng.integers(1, 1400))
         Nb = (N + blk - 1) // blk
-        amp = float(rng.choice([0.3, 1.0, 1.5]))
+        amp = float(rng.choice([0.3, 1.0, 1.5, 3.0]))
         pad = int(rng.choice([0, 8, 40]))
         gen = torch.Generator().manual_seed(int(rng.integers(0, 1 << 30)))
         q, k, v = ((amp * torch.randn((B, H, N, D + pad), generator=gen)).bfloat16() for _ in range(3))
@@ -57,8 +57,9 @@ def test_attention_random_cases(heart, seed):
         rows = np.repeat(kcnt > 0, blk, axis=2)[:, :, :N]
         assert np.all(got[~rows] == 0), "rows without kept blocks must be zero"
         if rows.any():
-            # (the budget is for inputs of unit scale; the error grows with the cube of the scale)
-            assert np.abs(got - want)[rows].max() <= ATTN_ATOL * max(1.0, amp ** 3)
+            # (2e-2 for outputs of unit scale, growing with the output's magnitude beyond 2)
+            err = np.abs(got - want)[rows].max()
+            assert err <= attn_atol(want), f"max abs err {err:.4f} > {attn_atol(want):.4f}"
 
 
 @pytest.mark.parametrize("seed", [201, 202])

@@ -12,7 +12,10 @@ import torch
 import oracle
 from oracle import antidiag_oracle
 from heart_synth import CONFIGS, HeartInputGenerator
-from heart_testlib import ATTN_ATOL, assert_masks_equal_up_to_threshold, gpu, np_gpu, u16
+from heart_testlib import (ATTN_ATOL, SCORE_RTOL, assert_masks_equal_up_to_threshold, gpu, np_gpu,
+                           pooled_mean_score_shift, u16)
+
+ANTIDIAG_SCORE_RTOL = 2e-3  # score tolerance of the antidiagonal-style estimator (fp32 sums of bf16 products)
 
 pytestmark = pytest.mark.gpu
 
@@ -91,9 +94,18 @@ def test_tmr_driver_matches_oracle_simulation(inputs, policy, estimator):
             n_refresh += int(orf.sum())
             n_reuse += int((1 - orf).sum())
             oracle.topp(osc, g.tau, refresh=orf, mask=o["mask"], kept_idx=o["idx"], kept_count=o["cnt"])
-            same = assert_masks_equal_up_to_threshold(drv.states[(layer, 0)].mask.cpu().numpy(), o["mask"],
-                                                      osc, o["cnt"], g.tau, f"{policy} step {s} layer {layer}",
-                                                      tol=1e-4 if estimator == "pooled" else 2e-3)
+            # heads refreshed in this call: rows may differ from the oracle's only where the
+            # cumulative mass passes within the estimator's score tolerance of the threshold
+            # (reused heads keep masks that were checked in the call that made them)
+            gm = drv.states[(layer, 0)].mask.cpu().numpy()
+            fresh = orf.astype(bool)[:, :, None, None]
+            shift = None
+            if estimator == "pooled" and orf.any():
+                shift = pooled_mean_score_shift(osc, drv.qblk, drv.kblk)
+            assert_masks_equal_up_to_threshold(np.where(fresh, gm, o["mask"]), o["mask"], osc, o["cnt"], g.tau,
+                                               f"{policy} step {s} layer {layer}", row_tol=shift,
+                                               tol=SCORE_RTOL if estimator == "pooled" else ANTIDIAG_SCORE_RTOL)
+            same = ~(gm != o["mask"]).any(-1)
             want = oracle.attn(qu, ku, vu, blk, o["idx"], o["cnt"])
             rows_same = np.repeat(same, blk, axis=2)[:, :, :N]
             assert np.abs(got - want)[rows_same].max() <= ATTN_ATOL
