@@ -202,6 +202,24 @@ int heart_block_sparse_attn_flags(const heart_shape *shape, const void *q_bf16,
                                   size_t workspace_bytes, void *stream);
 
 /*
+ * heart_block_sparse_attn_flags for callers that cannot allocate device memory or pass a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The launch plan lives in a static device array of the library
+ * (HEART_ATTN_STATIC_PLAN_BYTES on every GPU the library runs on, held until the process
+ * ends); the call allocates nothing and otherwise does what heart_block_sparse_attn_flags does
+ * with a workspace, with the same results.  It needs heart_workspace_bytes(B, H, Nb, D) <=
+ * HEART_ATTN_STATIC_PLAN_BYTES, i.e. B*H*(Nb+2) + 24 <= 262144, and returns HEART_EUNSUPPORTED
+ * beyond that.  Every call on a GPU shares that GPU's array (each call rebuilds the plan, so
+ * nothing carries over from the previous one): calls that overlap on one GPU -- different
+ * streams, or different host threads -- race; keep them stream-ordered.
+ */
+#define HEART_ATTN_STATIC_PLAN_BYTES (1u << 20)
+int heart_block_sparse_attn_static(const heart_shape *shape, const void *q_bf16,
+                                   const void *k_bf16, const void *v_bf16, const int *kept_idx,
+                                   const int *kept_count, float scale, unsigned flags,
+                                   void *out_bf16, float *lse, void *stream);
+
+/*
  * Bytes of workspace the hot path can use for one call: only heart_block_sparse_attn takes one
  * (its launch plan: 24 + B*H*(Nb+2) ints); heart_pool_qk, heart_drift and heart_mask_topp
  * need none.  heart_workspace_bytes takes plain sizes (D does not enter; it is part of the

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     heart_attn_workspace_bytes,
     heart_block_sparse_attn,
     heart_block_sparse_attn_flags,
+    heart_block_sparse_attn_static,
     heart_drift,
     heart_ebc_band_error,
     heart_ebc_select,

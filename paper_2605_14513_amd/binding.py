@@ -61,6 +61,8 @@ def load_library() -> ctypes.CDLL:
                                             ctypes.c_size_t, vp]
     lib.heart_block_sparse_attn_flags.argtypes = [sp, vp, vp, vp, vp, vp, cf, ctypes.c_uint, vp, vp,
                                                   vp, ctypes.c_size_t, vp]
+    lib.heart_block_sparse_attn_static.argtypes = [sp, vp, vp, vp, vp, vp, cf, ctypes.c_uint, vp, vp, vp]
+    lib.heart_block_sparse_attn_static.restype = ci
     lib.heart_attn_workspace_bytes.argtypes = [sp]
     lib.heart_attn_workspace_bytes.restype = ctypes.c_size_t
     lib.heart_workspace_bytes.argtypes = [ci, ci, ci, ci]
@@ -288,6 +290,29 @@ def heart_block_sparse_attn_flags(q, k, v, block: int, kept_idx, kept_count, fla
     """heart_block_sparse_attn with option flags (HEART_ATTN_FOLD_SCALE)."""
     return heart_block_sparse_attn(q, k, v, block, kept_idx, kept_count, scale=scale, out=out,
                                    lse=lse, workspace=workspace, flags=flags)
+
+
+def heart_block_sparse_attn_static(q, k, v, block: int, kept_idx, kept_count, out, flags: int = 0,
+                                   scale: float = 0.0, lse=None):
+    """heart_block_sparse_attn with the launch plan in the library's static device array: the
+    call allocates nothing (so `out` must be given)."""
+    lib = load_library()
+    if q.shape != k.shape or q.shape != v.shape or out.shape != q.shape:
+        raise ValueError("q, k, v, out must have the same shape")
+    B, H, N, D = q.shape
+    Nb = (N + block - 1) // block
+    if tuple(kept_idx.shape) != (B, H, Nb, Nb) or tuple(kept_count.shape) != (B, H, Nb):
+        raise ValueError("kept_idx must be [B,H,Nb,Nb] and kept_count [B,H,Nb]")
+    if lse is not None and tuple(lse.shape) != (B, H, N):
+        raise ValueError("lse must be [B,H,N]")
+    shape = make_shape(q, k, block, v, out)
+    rc = lib.heart_block_sparse_attn_static(
+        ctypes.byref(shape), _dev(q, torch.bfloat16, "q", False), _dev(k, torch.bfloat16, "k", False),
+        _dev(v, torch.bfloat16, "v", False), _dev(kept_idx, torch.int32, "kept_idx"),
+        _dev(kept_count, torch.int32, "kept_count"), float(scale), int(flags),
+        _dev(out, torch.bfloat16, "out", False), _dev(lse, torch.float32, "lse"), _stream())
+    _check("heart_block_sparse_attn_static", rc)
+    return out
 
 
 def heart_ubench_mfma_bf16(a, b, n_workgroups: int, iters: int, sink=None):

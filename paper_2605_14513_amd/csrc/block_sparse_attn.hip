@@ -884,4 +884,30 @@ int launch_attn(const heart_shape &s, const void *q, const void *k, const void *
   return launch_attn_e<true>(s, q, k, v, kept_idx, kept_count, scale, out, lse, order, st);
 }
 
+// ---- launch plan in static device memory, for callers that cannot allocate --------------------
+// One array per GPU (every device the library runs on holds its own copy at its own address
+// until the process ends).  In host code the array's name is only a stand-in for the symbol:
+// the device address is looked up once per device, with that device current, and only that
+// pointer is handed to kernels.
+static __device__ __align__(256) int g_plan_scratch[HEART_ATTN_STATIC_PLAN_BYTES / sizeof(int)];
+
+int attn_static_plan(int **ptr) {
+  const int dev = current_device();
+  if (dev < 0)
+    return fail(HEART_EHIP, "heart_block_sparse_attn_static: cannot identify the current device");
+  static std::atomic<int *> addr[kMaxDevices];
+  int *p = addr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    void *sym = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&sym, HIP_SYMBOL(g_plan_scratch));
+    if (e != hipSuccess || !sym)
+      return fail(HEART_EHIP, "heart_block_sparse_attn_static: hipGetSymbolAddress: %s",
+                  hipGetErrorString(e));
+    p = static_cast<int *>(sym);
+    addr[dev].store(p, std::memory_order_release);  // (threads that race store the same address)
+  }
+  *ptr = p;
+  return HEART_OK;
+}
+
 }  // namespace heart

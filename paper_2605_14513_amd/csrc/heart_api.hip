@@ -162,6 +162,24 @@ int heart_block_sparse_attn_flags(const heart_shape *shape, const void *q, const
                       workspace_bytes, stream);
 }
 
+int heart_block_sparse_attn_static(const heart_shape *shape, const void *q, const void *k,
+                                   const void *v, const int *kept_idx, const int *kept_count,
+                                   float scale, unsigned flags, void *out, float *lse,
+                                   void *stream) {
+  clear_error();
+  if (int rc = check_shape(shape, "heart_block_sparse_attn_static")) return rc;
+  const size_t need = heart_attn_workspace_bytes(shape);
+  if (need > HEART_ATTN_STATIC_PLAN_BYTES)
+    return fail(HEART_EUNSUPPORTED,
+                "heart_block_sparse_attn_static: the launch plan of this shape takes %zu bytes, the "
+                "static array holds %u (B*H*(Nb+2) + 24 ints must not exceed %u)",
+                need, HEART_ATTN_STATIC_PLAN_BYTES, HEART_ATTN_STATIC_PLAN_BYTES / 4u);
+  int *plan = nullptr;
+  if (int rc = attn_static_plan(&plan)) return rc;
+  return attn_checked(shape, q, k, v, kept_idx, kept_count, scale, flags, out, lse, plan, need,
+                      stream);
+}
+
 size_t heart_workspace_bytes(int B, int H, int Nb, int D) {
   (void)D;
   if (B <= 0 || H <= 0 || Nb <= 0) return 0;

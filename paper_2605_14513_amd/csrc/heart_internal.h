@@ -199,6 +199,10 @@ int launch_attn(const heart_shape &s, const void *q, const void *k, const void *
                 const int *kept_idx, const int *kept_count, float scale, unsigned flags, void *out,
                 float *lse, int *order, hipStream_t st);
 
+// Device address, on the current device, of the library's static launch-plan array
+// (HEART_ATTN_STATIC_PLAN_BYTES bytes).
+int attn_static_plan(int **ptr);
+
 int launch_antidiag(const heart_shape &s, const void *q, const void *k, int stride,
                     const unsigned char *refresh, float *scores, float *workspace, hipStream_t st);
 size_t antidiag_workspace_bytes(const heart_shape &s, int stride);
