@@ -39,6 +39,9 @@ def parse_args():
     ap.add_argument("--workload", default="wan14b_480p")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gate", default="0.4,0.8", help="layer gate lo,hi (0,1 disables)")
+    ap.add_argument("--unfused", action="store_true",
+                    help="call heart_pool_qk and heart_drift separately (three launches) instead of "
+                         "heart_pool_drift (two launches)")
     ap.add_argument("--fold-scale", action="store_true",
                     help="time the headline step with HEART_ATTN_FOLD_SCALE (softmax scale folded into "
                          "Q: one more bf16 rounding of the query, no per-logit multiply) instead of the "
@@ -425,6 +428,7 @@ def main():
     kcnt = torch.zeros((B, H, Nb), dtype=torch.int32, device=dev)
     out = torch.empty_like(steps_in[0][0])
     attn_ws = torch.empty(heart.heart_workspace_bytes(B, H, Nb, D), dtype=torch.uint8, device=dev)
+    tickets = torch.zeros(heart.heart_pool_drift_workspace_bytes(B, H), dtype=torch.uint8, device=dev)
     flags_main = heart.HEART_ATTN_FOLD_SCALE if args.fold_scale else 0
     flags_other = 0 if args.fold_scale else heart.HEART_ATTN_FOLD_SCALE
     path_name = {0: "fp32_scale (default)", heart.HEART_ATTN_FOLD_SCALE: "fold_scale"}
@@ -439,9 +443,14 @@ def main():
         if s == 0:
             has.zero_()  # schedule wraps: no cached anchors
         if ev: ev[0].record()
-        heart.heart_pool_qk(q, k, blk, qblk, kblk, qmean, kmean)
-        if ev and inner: ev[1].record()
-        heart.heart_drift(qmean, kmean, qa, ka, has, delta, gate[0], gate[1], True, drift, refresh)
+        if args.unfused:
+            heart.heart_pool_qk(q, k, blk, qblk, kblk, qmean, kmean)
+            if ev and inner: ev[1].record()
+            heart.heart_drift(qmean, kmean, qa, ka, has, delta, gate[0], gate[1], True, drift, refresh)
+        else:  # pooling pass, then token means + drift + reuse rule + gate in one launch
+            heart.heart_pool_drift(q, k, blk, qa, ka, has, delta, tickets, gate[0], gate[1], True,
+                                   qblk, kblk, qmean, kmean, drift, refresh)
+            if ev and inner: ev[1].record()
         if ev and inner: ev[2].record()
         heart.heart_mask_topp(qblk, kblk, tau, refresh=refresh, n_always_kv_blocks=nt,
                               n_dense_q_blocks=nt, mask=mask, kept_idx=kidx, kept_count=kcnt)
@@ -612,6 +621,8 @@ def main():
         },
         "mask_refresh_us_per_step": refresh_ms * 1e3,
         "launch_overhead": launch,
+        # (heart_pool_drift: "pool_qk" covers its two launches and "drift" is only an event gap)
+        "token_means_and_drift_share_a_launch": not args.unfused,
         "kernels_us": {"pool_qk": pool_ms * 1e3, "drift": drift_ms * 1e3,
                        "mask_topp": mask_ms * 1e3, "block_sparse_attn": attn_ms * 1e3},
         "attn_kept_tflops": attn_tflops,

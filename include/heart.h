@@ -5,6 +5,7 @@
  * One denoising step of one attention layer calls, in this order (the paper's
  * Temporal Mask Reuse procedure, Alg. 1):
  *     heart_pool_qk  ->  heart_drift  ->  heart_mask_topp  ->  heart_block_sparse_attn
+ * (heart_pool_drift does the first two with one launch fewer.)
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller (for instance the
@@ -12,7 +13,8 @@
  *     state between calls (beyond per-device launch attributes it sets once), reads no
  *     environment variable; an entry point that needs scratch memory takes it as a
  *     workspace argument.  Workspace sizes: heart_workspace_bytes (the hot path),
- *     heart_scores_antidiag_workspace_bytes, heart_ebc_workspace_bytes.
+ *     heart_pool_drift_workspace_bytes, heart_scores_antidiag_workspace_bytes,
+ *     heart_ebc_workspace_bytes.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call
  *     only enqueues kernels on that stream and returns; it never synchronises.
  *   - Return value: HEART_OK (0) or a negative error code.  After an error
@@ -93,6 +95,27 @@ int heart_pool_qk(const heart_shape *shape, const void *q_bf16, const void *k_bf
 int heart_drift(int B, int H, int D, const float *qmean, const float *kmean, float *qanchor,
                 float *kanchor, unsigned char *has_anchor, const float *delta, float gate_lo,
                 float gate_hi, int commit, float *drift, unsigned char *refresh, void *stream);
+
+/*
+ * heart_pool_qk and heart_drift in TWO launches instead of three (the paper observes that fixed
+ * per-layer cost such as kernel launches caps what mask reuse can gain: Sec. 4.2, last
+ * paragraph): the pooling pass, then one launch that computes the token means and, in the
+ * workgroup that finishes the last token mean of a batch item, the drift stage.  Arguments and
+ * results are those of the two calls: qblk, kblk, qmean, kmean are outputs as in heart_pool_qk
+ * (same bits); drift, refresh and the anchor update are what heart_drift gives on those qmean,
+ * kmean (same code, same bits).  No workgroup waits for another.
+ * workspace: device memory of heart_pool_drift_workspace_bytes(B, H) bytes, 4-byte aligned,
+ * holding the completion tickets.  It must be ZERO before the first call that uses it (e.g. one
+ * hipMemset after allocating it); every call leaves it zero again, so it can be reused from call
+ * to call.  Two calls that run concurrently must not share it.
+ * Limits: those of heart_pool_qk and heart_drift (D in {64, 128}, H <= 4096).
+ */
+int heart_pool_drift(const heart_shape *shape, const void *q_bf16, const void *k_bf16, float *qblk,
+                     float *kblk, float *qmean, float *kmean, float *qanchor, float *kanchor,
+                     unsigned char *has_anchor, const float *delta, float gate_lo, float gate_hi,
+                     int commit, float *drift, unsigned char *refresh, void *workspace,
+                     size_t workspace_bytes, void *stream);
+size_t heart_pool_drift_workspace_bytes(int B, int H);
 
 /*
  * Block importance and top-p block mask for refreshed heads (top-p rule of

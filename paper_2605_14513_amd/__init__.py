@@ -16,6 +16,8 @@ from .binding import (  # noqa: F401
     heart_ebc_workspace_bytes,
     heart_last_error,
     heart_mask_topp,
+    heart_pool_drift,
+    heart_pool_drift_workspace_bytes,
     heart_pool_qk,
     heart_scores_antidiag,
     heart_scores_antidiag_workspace_bytes,

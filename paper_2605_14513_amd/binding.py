@@ -59,6 +59,11 @@ def load_library() -> ctypes.CDLL:
                                     vp, vp]
     lib.heart_block_sparse_attn.argtypes = [sp, vp, vp, vp, vp, vp, cf, vp, vp, vp,
                                             ctypes.c_size_t, vp]
+    lib.heart_pool_drift.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, cf, cf, ci, vp, vp, vp,
+                                     ctypes.c_size_t, vp]
+    lib.heart_pool_drift.restype = ci
+    lib.heart_pool_drift_workspace_bytes.argtypes = [ci, ci]
+    lib.heart_pool_drift_workspace_bytes.restype = ctypes.c_size_t
     lib.heart_block_sparse_attn_flags.argtypes = [sp, vp, vp, vp, vp, vp, cf, ctypes.c_uint, vp, vp,
                                                   vp, ctypes.c_size_t, vp]
     lib.heart_block_sparse_attn_static.argtypes = [sp, vp, vp, vp, vp, vp, cf, ctypes.c_uint, vp, vp, vp]
@@ -185,6 +190,51 @@ def heart_drift(qmean, kmean, qanchor, kanchor, has_anchor, delta, gate_lo: floa
                          _dev(refresh, torch.uint8, "refresh"), _stream())
     _check("heart_drift", rc)
     return drift, refresh
+
+
+def heart_pool_drift_workspace_bytes(B: int, H: int) -> int:
+    return int(load_library().heart_pool_drift_workspace_bytes(int(B), int(H)))
+
+
+def heart_pool_drift(q, k, block: int, qanchor, kanchor, has_anchor, delta, workspace,
+                     gate_lo: float = 0.4, gate_hi: float = 0.8, commit: bool = True, qblk=None,
+                     kblk=None, qmean=None, kmean=None, drift=None, refresh=None):
+    """heart_pool_qk and heart_drift with one launch fewer (token means and drift share a launch).  workspace: a GPU tensor of at least
+    heart_pool_drift_workspace_bytes(B, H) bytes that was zero before its first use (the call
+    leaves it zero).  Returns (qblk, kblk, qmean, kmean, drift, refresh)."""
+    lib = load_library()
+    if q.shape != k.shape:
+        raise ValueError("q and k must have the same shape")
+    B, H, N, D = q.shape
+    Nb = (N + block - 1) // block
+    f32 = dict(dtype=torch.float32, device=q.device)
+    qblk = torch.empty((B, H, Nb, D), **f32) if qblk is None else qblk
+    kblk = torch.empty((B, H, Nb, D), **f32) if kblk is None else kblk
+    qmean = torch.empty((B, H, D), **f32) if qmean is None else qmean
+    kmean = torch.empty((B, H, D), **f32) if kmean is None else kmean
+    drift = torch.empty((B, H), **f32) if drift is None else drift
+    refresh = torch.empty((B, H), dtype=torch.uint8, device=q.device) if refresh is None else refresh
+    if delta.numel() != H:
+        raise ValueError("delta must have H entries")
+    for t, n in ((qanchor, "qanchor"), (kanchor, "kanchor"), (qmean, "qmean"), (kmean, "kmean")):
+        if tuple(t.shape) != (B, H, D):
+            raise ValueError(f"{n} must be [B,H,D]")
+    if tuple(has_anchor.shape) != (B, H) or tuple(drift.shape) != (B, H) or tuple(refresh.shape) != (B, H):
+        raise ValueError("has_anchor, drift, refresh must be [B,H]")
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous GPU tensor")
+    shape = make_shape(q, k, block)
+    rc = lib.heart_pool_drift(
+        ctypes.byref(shape), _dev(q, torch.bfloat16, "q", False), _dev(k, torch.bfloat16, "k", False),
+        _dev(qblk, torch.float32, "qblk"), _dev(kblk, torch.float32, "kblk"),
+        _dev(qmean, torch.float32, "qmean"), _dev(kmean, torch.float32, "kmean"),
+        _dev(qanchor, torch.float32, "qanchor"), _dev(kanchor, torch.float32, "kanchor"),
+        _dev(has_anchor, torch.uint8, "has_anchor"), _dev(delta, torch.float32, "delta"),
+        float(gate_lo), float(gate_hi), 1 if commit else 0, _dev(drift, torch.float32, "drift"),
+        _dev(refresh, torch.uint8, "refresh"), ctypes.c_void_p(workspace.data_ptr()),
+        workspace.numel() * workspace.element_size(), _stream())
+    _check("heart_pool_drift", rc)
+    return qblk, kblk, qmean, kmean, drift, refresh
 
 
 def heart_mask_topp(qblk, kblk, tau, refresh=None, scores_in=None, n_always_kv_blocks: int = 0,

@@ -67,6 +67,43 @@ int heart_pool_qk(const heart_shape *shape, const void *q, const void *k, float 
   return launch_pool(*shape, q, k, qblk, kblk, qmean, kmean, (hipStream_t)stream);
 }
 
+size_t heart_pool_drift_workspace_bytes(int B, int H) {
+  if (B <= 0 || H <= 0) return 0;
+  (void)H;
+  return (size_t)B * sizeof(unsigned);  // one completion ticket per batch item
+}
+
+int heart_pool_drift(const heart_shape *shape, const void *q, const void *k, float *qblk,
+                     float *kblk, float *qmean, float *kmean, float *qanchor, float *kanchor,
+                     unsigned char *has_anchor, const float *delta, float gate_lo, float gate_hi,
+                     int commit, float *drift, unsigned char *refresh, void *workspace,
+                     size_t workspace_bytes, void *stream) {
+  clear_error();
+  if (int rc = check_shape(shape, "heart_pool_drift")) return rc;
+  if (!q || !k || !qblk || !kblk || !qmean || !kmean || !qanchor || !kanchor || !has_anchor ||
+      !delta || !drift || !refresh || !workspace)
+    return fail(HEART_EINVAL, "heart_pool_drift: NULL pointer argument");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(qblk) || !aligned16(kblk) ||
+      !aligned16(qmean) || !aligned16(kmean))
+    return fail(HEART_EUNSUPPORTED, "heart_pool_drift: q, k and the pooled outputs must be 16-byte aligned");
+  if (!stride_ok(shape->q_stride) || !stride_ok(shape->k_stride))
+    return fail(HEART_EUNSUPPORTED,
+                "heart_pool_drift: strides must be multiples of 8 elements, token stride > 0");
+  if (shape->H > 4096)
+    return fail(HEART_EUNSUPPORTED, "heart_pool_drift: H must be <= 4096 (got %d)", shape->H);
+  if (!(gate_lo <= gate_hi))
+    return fail(HEART_EINVAL, "heart_pool_drift: need gate_lo <= gate_hi (got %g, %g)", gate_lo,
+                gate_hi);
+  if ((reinterpret_cast<uintptr_t>(workspace) & 3u) != 0)
+    return fail(HEART_EUNSUPPORTED, "heart_pool_drift: workspace must be 4-byte aligned");
+  if (workspace_bytes < heart_pool_drift_workspace_bytes(shape->B, shape->H))
+    return fail(HEART_EINVAL, "heart_pool_drift: workspace of %zu bytes, need %zu", workspace_bytes,
+                heart_pool_drift_workspace_bytes(shape->B, shape->H));
+  return launch_pool_drift(*shape, q, k, qblk, kblk, qmean, kmean, qanchor, kanchor, has_anchor,
+                           delta, gate_lo, gate_hi, commit, drift, refresh, (unsigned *)workspace,
+                           (hipStream_t)stream);
+}
+
 int heart_drift(int B, int H, int D, const float *qmean, const float *kmean, float *qanchor,
                 float *kanchor, unsigned char *has_anchor, const float *delta, float gate_lo,
                 float gate_hi, int commit, float *drift, unsigned char *refresh, void *stream) {

@@ -187,6 +187,11 @@ inline int cu_count(int dev) {
 // launchers implemented per kernel file
 int launch_pool(const heart_shape &s, const void *q, const void *k, float *qblk, float *kblk,
                 float *qmean, float *kmean, hipStream_t st);
+int launch_pool_drift(const heart_shape &s, const void *q, const void *k, float *qblk, float *kblk,
+                      float *qmean, float *kmean, float *qanchor, float *kanchor,
+                      unsigned char *has_anchor, const float *delta, float gate_lo, float gate_hi,
+                      int commit, float *drift, unsigned char *refresh, unsigned *tickets,
+                      hipStream_t st);
 int launch_drift(int B, int H, int D, const float *qmean, const float *kmean, float *qanchor,
                  float *kanchor, unsigned char *has_anchor, const float *delta, float gate_lo,
                  float gate_hi, int commit, float *drift, unsigned char *refresh,

@@ -31,11 +31,14 @@ namespace heart {
 
 constexpr int kRows = 16;      // query-block rows per workgroup (one MFMA tile high)
 constexpr int kMaxF4 = 8;      // float4 per lane and tile at D = 128 (D/16)
-constexpr int kWaves = 8;      // wavefronts per workgroup: two rows each in the selection
+constexpr int kWaves = 8;      // wavefronts per workgroup: two rows each per selection pass
 typedef __attribute__((ext_vector_type(4))) double f64x4_t;
 
-template <int CMAX>  // slots per lane; handles Nb <= 64 * CMAX
-__global__ __launch_bounds__(64 * kWaves) void mask_topp_kernel(
+// CMAX: slots per lane; handles Nb <= 64 * CMAX.  NF4T: D / 16 when known at compile time
+// (4 or 8), else 0: with it the contraction loop is branch-free, so that the loads of the next
+// tile stay in flight under the matrix instructions of the current one.
+template <int CMAX, int NF4T>
+__global__ __launch_bounds__(64 * kWaves, 4) void mask_topp_kernel(
     int H, int Nb, int D, const float *__restrict__ qblk, const float *__restrict__ kblk,
     const float *__restrict__ scores_in, const float *__restrict__ tau,
     const unsigned char *__restrict__ refresh, int n_always_kv, int n_dense_q, int min_keep,
@@ -46,6 +49,7 @@ __global__ __launch_bounds__(64 * kWaves) void mask_topp_kernel(
   float *sP = reinterpret_cast<float *>(smem_raw);  // [kRows][NBP] logits of the rows
   double *sQ = reinterpret_cast<double *>(smem_raw + (size_t)kRows * NBP * 4);  // [kRows][D + 2]
 
+  if (NF4T) D = 16 * NF4T;  // (a compile-time constant from here on)
   const int groups = (Nb + kRows - 1) / kRows;
   const long long bh = blockIdx.x / groups;
   const int i0 = (int)(blockIdx.x % groups) * kRows;
@@ -53,19 +57,42 @@ __global__ __launch_bounds__(64 * kWaves) void mask_topp_kernel(
   if (refresh && !refresh[bh]) return;  // reused head: cached mask persists
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#ifdef HEART_TOPP_TIMING
+  unsigned long long tt[8];
+  tt[0] = __builtin_amdgcn_s_memrealtime();
+#define TT(i) tt[i] = __builtin_amdgcn_s_memrealtime()
+#else
+#define TT(i)
+#endif
 
   if (!scores_in) {
     // ---- Phase A: logits -------------------------------------------------------
     // MFMA operand layout (16x16x4 fp64): A lane L = (row L%16, k L/16), B lane L =
     // (k L/16, column L%16), D lane L register r = (row L/16 + 4 r, column L%16).
     const int n16 = lane & 15, g = lane >> 4;
-    const int nf4 = D / 16;  // float4 per lane: its D/4 consecutive d values
+    const int nf4 = NF4T ? NF4T : D / 16;  // float4 per lane: its D/4 consecutive d values
     const float4 *qg = reinterpret_cast<const float4 *>(qblk + (size_t)bh * Nb * D);
     const float4 *kg = reinterpret_cast<const float4 *>(kblk + (size_t)bh * Nb * D);
+    const int SQ = D + 2;
+    const double *qrow = sQ + n16 * SQ + g * (D / 4);  // this lane's A operands, step by step
+    // (columns past Nb read the last key block instead of branching; their logits are not
+    // stored)
+    auto load_tile = [&](float4 (&dst)[kMaxF4], int tile) {
+      const int j = min(tile * 16 + n16, Nb - 1);
+#pragma unroll
+      for (int u = 0; u < kMaxF4; ++u) {
+        if (u < nf4)
+          dst[u] = kg[(size_t)j * (D / 4) + g * nf4 + u];
+        else
+          dst[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+    };
+    const double inv_sqrt_d = 1.0 / sqrt((double)D);
+    const int ntiles = (Nb + 15) / 16;
+    float4 kc[kMaxF4], kn[kMaxF4];
     // the 16 query rows as fp64 in LDS (row stride D + 2 doubles: the 16 rows a quarter of
     // the lanes reads fall into distinct banks); keeping them there rather than in 64
     // registers lets more wavefronts share a SIMD, which the latency-bound selection needs
-    const int SQ = D + 2;
     for (int e = threadIdx.x; e < kRows * (D / 4); e += 64 * kWaves) {
       const int r = e / (D / 4), d4 = e % (D / 4);
       float4 t4 = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -77,20 +104,12 @@ __global__ __launch_bounds__(64 * kWaves) void mask_topp_kernel(
       dst[3] = (double)t4.w;
     }
     __syncthreads();
-    const double *qrow = sQ + n16 * SQ + g * (D / 4);  // this lane's A operands, step by step
-    auto load_tile = [&](float4 (&dst)[kMaxF4], int tile) {
-      const int j = tile * 16 + n16;
-#pragma unroll
-      for (int u = 0; u < kMaxF4; ++u) {
-        dst[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (u < nf4 && j < Nb) dst[u] = kg[(size_t)j * (D / 4) + g * nf4 + u];
-      }
-    };
-    const double inv_sqrt_d = 1.0 / sqrt((double)D);
-    const int ntiles = (Nb + 15) / 16;
-    float4 kc[kMaxF4], kn[kMaxF4];
+    TT(1);
     if (wave < ntiles) load_tile(kc, wave);
     for (int tile = wave; tile < ntiles; tile += kWaves) {
+      // (compiler barrier: the query operands are re-read from LDS for every tile; hoisted out
+      // of the loop they would cost 64 registers and a wavefront per SIMD)
+      asm volatile("" ::: "memory");
       if (tile + kWaves < ntiles) load_tile(kn, tile + kWaves);
       f64x4_t acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
@@ -110,7 +129,9 @@ __global__ __launch_bounds__(64 * kWaves) void mask_topp_kernel(
 #pragma unroll
       for (int u = 0; u < kMaxF4; ++u) kc[u] = kn[u];
     }
+    TT(2);
     __syncthreads();
+    TT(3);
   }
 
   const float tau_h = tau[h];
@@ -127,7 +148,9 @@ __global__ __launch_bounds__(64 * kWaves) void mask_topp_kernel(
     constexpr int EPL = 2 * CMAX;  // elements per lane: element c is key block l32 + 32 c
     const int l32 = lane & 31, hfw = lane >> 5;
     const uint32_t lt32 = (1u << l32) - 1u;
-    const int r = 2 * wave + hfw;
+    static_assert(kRows % (2 * kWaves) == 0, "rows per selection pass");
+    for (int rp = 0; rp < kRows / (2 * kWaves); ++rp) {
+    const int r = 2 * (wave + rp * kWaves) + hfw;
     const int i = i0 + r;
     const bool row_ok = i < Nb;
     const size_t row = (size_t)bh * Nb + (row_ok ? i : 0);
@@ -154,6 +177,8 @@ __global__ __launch_bounds__(64 * kWaves) void mask_topp_kernel(
 #pragma unroll
       for (int c = 0; c < EPL; ++c) p[c] = __fdiv_rn(p[c], z);
     }
+    TT(4);
+#ifndef HEART_TOPP_TIMING
     if (scores_out && row_ok) {
 #pragma unroll
       for (int c = 0; c < EPL; ++c) {
@@ -161,6 +186,7 @@ __global__ __launch_bounds__(64 * kWaves) void mask_topp_kernel(
         if (j < Nb) scores_out[row * Nb + j] = p[c];
       }
     }
+#endif
     uint32_t e[EPL], u[EPL];
     uint32_t my_u = 0;
 #pragma unroll
@@ -258,6 +284,7 @@ __global__ __launch_bounds__(64 * kWaves) void mask_topp_kernel(
         }
       }
     }
+    TT(5);
     const bool dense_row = i < n_dense_q;
     int tie_run = 0, out_run = 0;
 #pragma unroll
@@ -279,6 +306,14 @@ __global__ __launch_bounds__(64 * kWaves) void mask_topp_kernel(
       if (keep) kept_idx[row * Nb + pos] = j;
     }
     if (l32 == 0 && row_ok) kept_count[row] = out_run;
+#ifdef HEART_TOPP_TIMING
+    TT(6);
+    if (l32 == 0 && row_ok && scores_out) {
+      for (int x = 1; x <= 6; ++x) scores_out[row * Nb + x] = (float)(tt[x] - tt[0]);
+      scores_out[row * Nb + 0] = (float)(tt[0] & 0xffffffull);
+    }
+#endif
+    }  // selection passes
     return;
   }
 
@@ -436,8 +471,8 @@ __global__ __launch_bounds__(64 * kWaves) void mask_topp_kernel(
   }
 }
 
-template <int CMAX>
-static int launch_cmax(int B, int H, int Nb, int D, const float *qblk, const float *kblk,
+template <int CMAX, int NF4T>
+static int launch_cmax_d(int B, int H, int Nb, int D, const float *qblk, const float *kblk,
                        const float *scores_in, const float *tau, const unsigned char *refresh,
                        int n_always_kv, int n_dense_q, int min_keep, unsigned char *mask,
                        int *kept_idx, int *kept_count, float *scores_out, hipStream_t st) {
@@ -448,14 +483,29 @@ static int launch_cmax(int B, int H, int Nb, int D, const float *qblk, const flo
     const int dev = current_device();
     if (dev < 0) return fail(HEART_EHIP, "heart_mask_topp: cannot identify the current device");
     static DeviceFlags attr_set;  // per instantiation: the attribute is per function and device
-    if (hipError_t e = set_max_lds_once(attr_set, dev, reinterpret_cast<const void *>(mask_topp_kernel<CMAX>),
-                                        96 * 1024))
+    if (hipError_t e = set_max_lds_once(attr_set, dev,
+                                        reinterpret_cast<const void *>(mask_topp_kernel<CMAX, NF4T>), 96 * 1024))
       return fail(HEART_EHIP, "hipFuncSetAttribute(mask kernel LDS): %s", hipGetErrorString(e));
   }
-  hipLaunchKernelGGL(mask_topp_kernel<CMAX>, dim3((unsigned)nwg), dim3(64 * kWaves), lds, st, H, Nb, D,
-                     qblk, kblk, scores_in, tau, refresh, n_always_kv, n_dense_q, min_keep, mask,
-                     kept_idx, kept_count, scores_out);
+  hipLaunchKernelGGL((mask_topp_kernel<CMAX, NF4T>), dim3((unsigned)nwg), dim3(64 * kWaves), lds, st, H,
+                     Nb, D, qblk, kblk, scores_in, tau, refresh, n_always_kv, n_dense_q, min_keep,
+                     mask, kept_idx, kept_count, scores_out);
   return check_launch("mask_topp_kernel");
+}
+
+template <int CMAX>
+static int launch_cmax(int B, int H, int Nb, int D, const float *qblk, const float *kblk,
+                       const float *scores_in, const float *tau, const unsigned char *refresh,
+                       int n_always_kv, int n_dense_q, int min_keep, unsigned char *mask,
+                       int *kept_idx, int *kept_count, float *scores_out, hipStream_t st) {
+#define HEART_TOPP_D_ARGS                                                                     \
+  B, H, Nb, D, qblk, kblk, scores_in, tau, refresh, n_always_kv, n_dense_q, min_keep, mask,   \
+      kept_idx, kept_count, scores_out, st
+  // the head dimensions of the attention kernels get a contraction loop of their own
+  if (!scores_in && D == 128) return launch_cmax_d<CMAX, 8>(HEART_TOPP_D_ARGS);
+  if (!scores_in && D == 64) return launch_cmax_d<CMAX, 4>(HEART_TOPP_D_ARGS);
+  return launch_cmax_d<CMAX, 0>(HEART_TOPP_D_ARGS);
+#undef HEART_TOPP_D_ARGS
 }
 
 int launch_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float *kblk,

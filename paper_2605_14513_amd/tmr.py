@@ -5,7 +5,7 @@ mask and its kept-block lists -- belongs to the caller, one set per (layer, clas
 guidance branch) as in the paper's cache (Sec. 4.2).  This module owns that state for a stack
 of attention layers and sequences the calls of one attention invocation:
 
-    heart   pool -> drift (reuse rule + layer gate, Alg. 1) -> mask for refreshed heads -> attention
+    heart   pool + drift, token means and drift sharing a launch (reuse rule + layer gate, Alg. 1) -> mask for refreshed heads -> attention
     always  pool -> mask for every head -> attention              (no reuse)
     interval:k   every head refreshes on every k-th sparse step, otherwise every head reuses
                  (the shared fixed-interval schedule the paper compares with, Sec. 5 ablations)
@@ -99,6 +99,9 @@ class TmrDriver:
         self.qmean = torch.empty((B, H, D), **f32)
         self.kmean = torch.empty((B, H, D), **f32)
         self.workspace: Optional[torch.Tensor] = None
+        # completion tickets of the fused pooling + drift launch (zero now, zero after every call)
+        self.tickets = torch.zeros(_b.heart_pool_drift_workspace_bytes(B, H), dtype=torch.uint8,
+                                   device=self.device)
         if cfg.estimator not in ("pooled", "antidiag"):
             raise ValueError(f"unknown importance estimator {cfg.estimator!r}")
         # scores and records of the antidiagonal-style estimator, shared by all layers
@@ -193,10 +196,11 @@ class TmrDriver:
         else:
             if self.policy == "heart":
                 kind = "heart"
-                _b.heart_pool_qk(q, k, cfg.block, self.qblk, self.kblk, self.qmean, self.kmean)
+                # pooling pass, then token means + drift + reuse rule + gate in one launch
+                _b.heart_pool_drift(q, k, cfg.block, st.qanchor, st.kanchor, st.has_anchor, cfg.delta,
+                                    self.tickets, cfg.gate[0], cfg.gate[1], True, self.qblk, self.kblk,
+                                    self.qmean, self.kmean, st.drift, st.refresh)
                 mark()
-                _b.heart_drift(self.qmean, self.kmean, st.qanchor, st.kanchor, st.has_anchor,
-                               cfg.delta, cfg.gate[0], cfg.gate[1], True, st.drift, st.refresh)
                 mark()
                 refresh_mask(st.refresh)
                 mark()

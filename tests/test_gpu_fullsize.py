@@ -137,6 +137,7 @@ def test_chained_full_size_steps_match_oracle(heart):
     gidx = torch.zeros((B, H, Nb, Nb), dtype=torch.int32, device=dev)
     gcnt = torch.zeros((B, H, Nb), dtype=torch.int32, device=dev)
     ws = torch.empty(heart.heart_workspace_bytes(B, H, Nb, D), dtype=torch.uint8, device=dev)
+    tickets = torch.zeros(heart.heart_pool_drift_workspace_bytes(B, H), dtype=torch.uint8, device=dev)
     chain = OracleChain(cfg, g.tau, g.delta)
     gtau, gdelta = np_gpu(g.tau), np_gpu(g.delta)
     rng = np.random.default_rng(cfg.seed + 1)
@@ -146,12 +147,13 @@ def test_chained_full_size_steps_match_oracle(heart):
         st = g.step(s)
         print(f"[{name}] chained step {s}", flush=True)
         q, k, v = gpu(st.q), gpu(st.k), gpu(st.v)
-        qblk, kblk, qmean, kmean = heart.heart_pool_qk(q, k, blk)
-        d, r = heart.heart_drift(qmean, kmean, gq, gk, gh, gdelta, 0.4, 0.8)
+        # (the calls bench.py times: token means and drift share a launch)
+        qblk, kblk, qmean, kmean, d, r = heart.heart_pool_drift(q, k, blk, gq, gk, gh, gdelta, tickets, 0.4, 0.8)
         heart.heart_mask_topp(qblk, kblk, gtau, refresh=r, n_always_kv_blocks=nt, n_dense_q_blocks=nt,
                               mask=gmask, kept_idx=gidx, kept_count=gcnt)
         out = heart.heart_block_sparse_attn(q, k, v, blk, gidx, gcnt, workspace=ws)
         torch.cuda.synchronize()
+        assert not tickets.any().item()
         od, orf = chain.step(st)
         assert np.array_equal(r.cpu().numpy(), orf), f"step {s}: refresh decisions differ"
         assert np.array_equal(gh.cpu().numpy(), chain.has)

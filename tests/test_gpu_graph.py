@@ -49,15 +49,17 @@ def test_captured_step_replays_bit_exact(estimator):
             out=torch.zeros((B, H, N, D), dtype=torch.bfloat16, device=dev),
             ws=torch.empty(heart.heart_attn_workspace_bytes(
                 torch.empty((B, H, N, D), dtype=torch.bfloat16, device=dev), blk), dtype=torch.uint8, device=dev),
+            tickets=torch.zeros(heart.heart_pool_drift_workspace_bytes(B, H), dtype=torch.uint8, device=dev),
             scores=torch.zeros((B, H, Nb, Nb), **f32),
             ews=torch.empty(heart.heart_scores_antidiag_workspace_bytes(
                 torch.empty((B, H, N, D), dtype=torch.bfloat16, device=dev), blk, blk // 8),
                 dtype=torch.uint8, device=dev))
 
     def step(s):
-        heart.heart_pool_qk(s["q"], s["k"], blk, s["qblk"], s["kblk"], s["qmean"], s["kmean"])
-        heart.heart_drift(s["qmean"], s["kmean"], s["qa"], s["ka"], s["has"], delta, 0.4, 0.8, True,
-                          s["drift"], s["refresh"])
+        # pooling pass, then token means, drift and gate in one launch (its ticket counters return to zero
+        # by themselves, which a replayed graph relies on)
+        heart.heart_pool_drift(s["q"], s["k"], blk, s["qa"], s["ka"], s["has"], delta, s["tickets"], 0.4, 0.8,
+                               True, s["qblk"], s["kblk"], s["qmean"], s["kmean"], s["drift"], s["refresh"])
         if estimator == "pooled":
             heart.heart_mask_topp(s["qblk"], s["kblk"], tau, refresh=s["refresh"], n_always_kv_blocks=nt,
                                   n_dense_q_blocks=nt, mask=s["mask"], kept_idx=s["kidx"], kept_count=s["kcnt"])

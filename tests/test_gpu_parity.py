@@ -148,6 +148,70 @@ def test_drift_hand_example_and_commit_off(heart):
         assert np.array_equal(gq.cpu().numpy(), qa)  # commit off: anchors untouched
 
 
+# ------------------------------------------------------------------------------ fused P1 + P2
+@pytest.mark.parametrize("name", SMALL)
+@pytest.mark.parametrize("gate", [(0.0, 1.0), (0.4, 0.8)])
+def test_pool_drift_equals_the_two_calls(heart, name, gate):
+    """heart_pool_drift over the whole schedule with carried anchors: every output has the bits
+    of heart_pool_qk followed by heart_drift, the decisions are the oracle's, and the ticket
+    workspace is zero again after every call."""
+    g, _ = case(name)
+    cfg = g.cfg
+    B, H, D = cfg.B, cfg.H, cfg.D
+    dev = "cuda"
+    f32 = dict(dtype=torch.float32, device=dev)
+    state = [dict(qa=torch.zeros((B, H, D), **f32), ka=torch.zeros((B, H, D), **f32),
+                  has=torch.zeros((B, H), dtype=torch.uint8, device=dev)) for _ in range(2)]
+    ws = torch.zeros(heart.heart_pool_drift_workspace_bytes(B, H) // 4 + 2, dtype=torch.int32, device=dev)
+    oq, ok_, oh = np.zeros((B, H, D), np.float32), np.zeros((B, H, D), np.float32), np.zeros((B, H), np.uint8)
+    gdelta = np_gpu(g.delta)
+    for s in range(cfg.steps):
+        _, st = case(name, s)
+        print(f"fused pool+drift {name} gate={gate} step {s}", flush=True)
+        q, k = gpu(st.q), gpu(st.k)
+        if s % 2:  # alternate the memory layout: [B,N,H,D] storage on odd steps
+            q = q.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+            k = k.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+        a, f = state
+        qblk, kblk, qmean, kmean = heart.heart_pool_qk(q, k, cfg.block)
+        d, r = heart.heart_drift(qmean, kmean, a["qa"], a["ka"], a["has"], gdelta, gate[0], gate[1])
+        fq, fk, fqm, fkm, fd, fr = heart.heart_pool_drift(q, k, cfg.block, f["qa"], f["ka"], f["has"], gdelta,
+                                                          ws, gate[0], gate[1])
+        torch.cuda.synchronize()
+        for x, y, what in ((fq, qblk, "qblk"), (fk, kblk, "kblk"), (fqm, qmean, "qmean"), (fkm, kmean, "kmean"),
+                           (fd, d, "drift"), (fr, r, "refresh"), (f["qa"], a["qa"], "qanchor"),
+                           (f["ka"], a["ka"], "kanchor"), (f["has"], a["has"], "has_anchor")):
+            assert torch.equal(x, y), f"step {s}: {what} differs between the fused and the separate calls"
+        assert not ws.any().item(), "the ticket workspace is zero again after the call"
+        # and against the oracle: decisions exact, means within the pooling tolerance
+        oqb, oqm = oracle.pool(u16(st.q), cfg.block)
+        okb, okm = oracle.pool(u16(st.k), cfg.block)
+        od, orf = oracle.drift(oqm, okm, oq, ok_, oh, g.delta, gate[0], gate[1])
+        assert np.array_equal(fr.cpu().numpy(), orf) and np.array_equal(f["has"].cpu().numpy(), oh)
+        amax = float(max(st.q.float().abs().max(), st.k.float().abs().max()))
+        assert_means_close(fqm, oqm, amax, "q token means")
+        assert_means_close(fkm, okm, amax, "k token means")
+        assert_means_close(fq, oqb, amax, "q block means")
+
+
+def test_pool_drift_commit_off_and_validation(heart):
+    g, st = case("small_d64")
+    cfg = g.cfg
+    B, H, D = cfg.B, cfg.H, cfg.D
+    q, k = gpu(st.q), gpu(st.k)
+    qa = torch.ones((B, H, D), device="cuda"); ka = torch.ones((B, H, D), device="cuda")
+    has = torch.ones((B, H), dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(heart.heart_pool_drift_workspace_bytes(B, H), dtype=torch.uint8, device="cuda")
+    out = heart.heart_pool_drift(q, k, cfg.block, qa, ka, has, np_gpu(np.full(H, 1e-3, np.float32)), ws,
+                                 0.0, 1.0, commit=False)
+    torch.cuda.synchronize()
+    assert out[5].all().item()                     # far from the anchors: every head refreshes
+    assert (qa == 1).all().item() and (ka == 1).all().item()  # commit off: anchors untouched
+    assert not ws.any().item()
+    with pytest.raises(heart.HeartError):
+        heart.heart_pool_drift(q, k, cfg.block, qa, ka, has, np_gpu(g.delta), ws[:-1])
+
+
 # ------------------------------------------------------------------------------ P3
 @pytest.mark.parametrize("name", SMALL)
 def test_scores_match_oracle(heart, name):
