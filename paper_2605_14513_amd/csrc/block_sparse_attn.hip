@@ -274,12 +274,14 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   constexpr int IPW = kStageRows / RPI / NW;  // such instructions per wavefront and tile
   constexpr int NSL = BLK / 32;          // 32-key slices per key block
   constexpr int SO = D + 8;              // LDS row stride of the output staging (elements)
-  // kExact: accumulators, maxima and the reference exponent are in raw logit units and
-  // kLogitScale takes them to log2 units where they enter an exponential; otherwise the
-  // accumulators already are in log2 units.  The running reference may lag the maximum by
-  // 8 log2 units.
-  const float kLogitScale = kExact ? scale_log2e : 1.f;
-  const float kRescaleSlack = kExact ? 8.f / scale_log2e : 8.f;
+  // kExact: S^T comes out of the matrix cores in raw logit units and is multiplied by
+  // scale * log2(e) in fp32 as soon as it is complete (in slots of the MFMA stream that have
+  // VALU time to spare: where the maximum is folded), so that from there on both variants
+  // hold logits in log2 units relative to the reference exponent.  The accumulators start
+  // from -m_ref, which kExact therefore converts back to raw units (kInitScale).  The running
+  // reference may lag the maximum by 8 log2 units.
+  const float kInitScale = kExact ? 1.f / scale_log2e : 1.f;
+  constexpr float kRescaleSlack = 8.f;
   static_assert(NW % 2 == 0 && IPW >= 1 && (NSL == 2 || NSL == 4), "tile layout");
 
   // LDS: [K stage 0][K stage 1][V stage 0][V stage 1], reused for the output at the end
@@ -488,10 +490,10 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
     // (the empty asm statements pin each result to its slot: without them the compiler
     // sinks the whole computation to its first use, out of the MFMA shadow)
     if (st == 0) {
-      xt0 = __builtin_amdgcn_exp2f(kExact ? x[r] * kLogitScale : x[r]);
+      xt0 = __builtin_amdgcn_exp2f(x[r]);
       asm volatile("" : "+v"(xt0));
     } else if (st == 1) {
-      xt1 = __builtin_amdgcn_exp2f(kExact ? x[r + 1] * kLogitScale : x[r + 1]);
+      xt1 = __builtin_amdgcn_exp2f(x[r + 1]);
       asm volatile("" : "+v"(xt1));
     } else {
       // (plain adds for the row sum: they co-issue with MFMAs, dot instructions do not)
@@ -552,7 +554,7 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
       const float base = first ? 0.f : m_ref;       // what the accumulators are relative to
       const float delta = bump ? m_rel : 0.f;
       const float m_new = bump ? base + m_rel : m_ref;
-      const float alpha = bump ? __builtin_amdgcn_exp2f((m_ref - m_new) * kLogitScale) : 1.f;  // 0 the first time
+      const float alpha = bump ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.f;  // 0 the first time
       l_run *= alpha;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
@@ -561,7 +563,7 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) x[r] -= delta;
       m_ref = m_new;
-      const float c0 = m_ref == -__builtin_inff() ? 0.f : -m_ref;
+      const float c0 = m_ref == -__builtin_inff() ? 0.f : -m_ref * kInitScale;
 #pragma unroll
       for (int r = 0; r < 16; ++r) cinit[r] = c0;
     }
@@ -571,7 +573,7 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   // sacc[cur ^ 1], whose MFMAs were issued before this phase and have drained by then.
   auto pv_step = [&](int cur, int g0) __attribute__((always_inline)) -> float {
     float m_loc = -__builtin_inff();
-    const f32x16_t &nx = sacc[cur ^ 1];
+    f32x16_t &nx = sacc[cur ^ 1];
     const f32x16_t &cx = sacc[cur];
 #pragma unroll
     for (int m = 0; m < NPV; ++m) {
@@ -583,7 +585,14 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
       }
       if (m >= DT) {
 #pragma unroll
-        for (int i = 0; i < 4 / DT; ++i) m_loc = max_part(nx, (m - DT) * (4 / DT) + i, m_loc);
+        for (int i = 0; i < 4 / DT; ++i) {
+          const int part = (m - DT) * (4 / DT) + i;
+          if constexpr (kExact) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) nx[4 * part + e] *= scale_log2e;  // raw logits -> log2 units
+          }
+          m_loc = max_part(nx, part, m_loc);
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -672,6 +681,10 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
         Frag8 a;
         a.u = fetch(3 * STEP + ks);  // K of slice 0: buffer 0, rows 0
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, qf[ks].v, acc, 0, 0, 0);
+      }
+      if constexpr (kExact) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] *= scale_log2e;
       }
       sacc[0] = acc;
       const int nv = N - k0;
@@ -768,7 +781,7 @@ __global__ __launch_bounds__(BLK * 2, HEART_ATTN_OCC) void attn_kernel(
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   if (lse && hf == 0 && qrow < N)
     lse[(size_t)bh * N + qrow] =
-        l_tot > 0.f ? (m_ref * kLogitScale + log2f(l_tot)) * 0.6931471805599453f : -__builtin_inff();
+        l_tot > 0.f ? (m_ref + log2f(l_tot)) * 0.6931471805599453f : -__builtin_inff();
   uint16_t *sO = reinterpret_cast<uint16_t *>(smem);  // [BLK][SO]
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)

@@ -9,6 +9,7 @@
 namespace heart {
 
 constexpr int kDriftMaxSlots = 8;  // D <= 512
+constexpr int kDriftHeadsPerPass = 4;
 
 // lds: 2 H bytes of LDS (marks, then final decisions).  Every lane of the workgroup must
 // call this (it contains workgroup barriers).  kAcross: qmean and kmean were written by other
@@ -33,43 +34,55 @@ __device__ __forceinline__ void drift_workgroup(
   const int n_waves = blockDim.x >> 6;
   const int slots = D > 64 ? D / 64 : 1;
 
-  for (int h = wave; h < H; h += n_waves) {
-    size_t o = ((size_t)b * H + h) * D;
-    // all loads are issued unconditionally (the anchor buffers always exist); a head
-    // without an anchor ignores the value
-    const bool has = has_anchor[(size_t)b * H + h] != 0;
-    const float dl = delta[h];
-    float a[kDriftMaxSlots];
+  // A wavefront takes kDriftHeadsPerPass heads at a time and issues the loads of all of them
+  // before it reduces any: the stage is bound by dependent memory round trips, not by bandwidth.
+  for (int h0 = wave * kDriftHeadsPerPass; h0 < H; h0 += n_waves * kDriftHeadsPerPass) {
+    float a[kDriftHeadsPerPass][kDriftMaxSlots];
+    bool has[kDriftHeadsPerPass];
+    float dl[kDriftHeadsPerPass];
 #pragma unroll
-    for (int c = 0; c < kDriftMaxSlots; ++c) {
-      a[c] = 0.f;
-      int d = lane + 64 * c;
-      if (c < slots && d < D) {
-        float dq = fabsf(qanchor[o + d] - cur(qmean + o + d));
-        float dk = fabsf(kanchor[o + d] - cur(kmean + o + d));
-        a[c] = dq + dk;
+    for (int u = 0; u < kDriftHeadsPerPass; ++u) {
+      const int h = min(h0 + u, H - 1);  // (a repeated last head is computed and not stored)
+      const size_t o = ((size_t)b * H + h) * D;
+      // all loads are issued unconditionally (the anchor buffers always exist); a head
+      // without an anchor ignores the value
+      has[u] = has_anchor[(size_t)b * H + h] != 0;
+      dl[u] = delta[h];
+#pragma unroll
+      for (int c = 0; c < kDriftMaxSlots; ++c) {
+        a[u][c] = 0.f;
+        const int d = lane + 64 * c;
+        if (c < slots && d < D) {
+          const float dq = fabsf(qanchor[o + d] - cur(qmean + o + d));
+          const float dk = fabsf(kanchor[o + d] - cur(kmean + o + d));
+          a[u][c] = dq + dk;
+        }
       }
     }
-    // steps with s >= 64: a[i] += a[i+s]  <=>  slot c += slot c + s/64
 #pragma unroll
-    for (int s = kDriftMaxSlots / 2; s >= 1; s >>= 1) {
-      if (s < slots) {
+    for (int u = 0; u < kDriftHeadsPerPass; ++u) {
+      const int h = h0 + u;
+      // steps with s >= 64: a[i] += a[i+s]  <=>  slot c += slot c + s/64
 #pragma unroll
-        for (int c = 0; c < kDriftMaxSlots / 2; ++c)
-          if (c < s) a[c] = a[c] + a[c + s];
+      for (int s = kDriftMaxSlots / 2; s >= 1; s >>= 1) {
+        if (s < slots) {
+#pragma unroll
+          for (int c = 0; c < kDriftMaxSlots / 2; ++c)
+            if (c < s) a[u][c] = a[u][c] + a[u][c + s];
+        }
       }
-    }
-    float v = a[0];
-    // steps with s < 64 (lanes >= D hold +0, adding it is exact)
+      float v = a[u][0];
+      // steps with s < 64 (lanes >= D hold +0, adding it is exact)
 #pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) {
-      float o2 = __shfl_xor(v, s, 64);
-      if (s < D) v = v + o2;
-    }
-    if (lane == 0) {
-      float dv = has ? v : __builtin_inff();
-      drift[(size_t)b * H + h] = dv;
-      mark[h] = (!has || dv > dl) ? 1 : 0;
+      for (int s = 32; s >= 1; s >>= 1) {
+        float o2 = __shfl_xor(v, s, 64);
+        if (s < D) v = v + o2;
+      }
+      if (lane == 0 && h < H) {
+        float dv = has[u] ? v : __builtin_inff();
+        drift[(size_t)b * H + h] = dv;
+        mark[h] = (!has[u] || dv > dl[u]) ? 1 : 0;
+      }
     }
   }
   __syncthreads();

@@ -57,13 +57,6 @@ __global__ __launch_bounds__(64 * kWaves, 4) void mask_topp_kernel(
   if (refresh && !refresh[bh]) return;  // reused head: cached mask persists
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#ifdef HEART_TOPP_TIMING
-  unsigned long long tt[8];
-  tt[0] = __builtin_amdgcn_s_memrealtime();
-#define TT(i) tt[i] = __builtin_amdgcn_s_memrealtime()
-#else
-#define TT(i)
-#endif
 
   if (!scores_in) {
     // ---- Phase A: logits -------------------------------------------------------
@@ -104,7 +97,6 @@ __global__ __launch_bounds__(64 * kWaves, 4) void mask_topp_kernel(
       dst[3] = (double)t4.w;
     }
     __syncthreads();
-    TT(1);
     if (wave < ntiles) load_tile(kc, wave);
     for (int tile = wave; tile < ntiles; tile += kWaves) {
       // (compiler barrier: the query operands are re-read from LDS for every tile; hoisted out
@@ -129,9 +121,7 @@ __global__ __launch_bounds__(64 * kWaves, 4) void mask_topp_kernel(
 #pragma unroll
       for (int u = 0; u < kMaxF4; ++u) kc[u] = kn[u];
     }
-    TT(2);
     __syncthreads();
-    TT(3);
   }
 
   const float tau_h = tau[h];
@@ -177,8 +167,6 @@ __global__ __launch_bounds__(64 * kWaves, 4) void mask_topp_kernel(
 #pragma unroll
       for (int c = 0; c < EPL; ++c) p[c] = __fdiv_rn(p[c], z);
     }
-    TT(4);
-#ifndef HEART_TOPP_TIMING
     if (scores_out && row_ok) {
 #pragma unroll
       for (int c = 0; c < EPL; ++c) {
@@ -186,7 +174,6 @@ __global__ __launch_bounds__(64 * kWaves, 4) void mask_topp_kernel(
         if (j < Nb) scores_out[row * Nb + j] = p[c];
       }
     }
-#endif
     uint32_t e[EPL], u[EPL];
     uint32_t my_u = 0;
 #pragma unroll
@@ -284,7 +271,6 @@ __global__ __launch_bounds__(64 * kWaves, 4) void mask_topp_kernel(
         }
       }
     }
-    TT(5);
     const bool dense_row = i < n_dense_q;
     int tie_run = 0, out_run = 0;
 #pragma unroll
@@ -306,13 +292,6 @@ __global__ __launch_bounds__(64 * kWaves, 4) void mask_topp_kernel(
       if (keep) kept_idx[row * Nb + pos] = j;
     }
     if (l32 == 0 && row_ok) kept_count[row] = out_run;
-#ifdef HEART_TOPP_TIMING
-    TT(6);
-    if (l32 == 0 && row_ok && scores_out) {
-      for (int x = 1; x <= 6; ++x) scores_out[row * Nb + x] = (float)(tt[x] - tt[0]);
-      scores_out[row * Nb + 0] = (float)(tt[0] & 0xffffffull);
-    }
-#endif
     }  // selection passes
     return;
   }

@@ -39,6 +39,7 @@ namespace heart {
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int kPoolThreads = 256;
+constexpr int kTokenMeanBatch = 16;  // block means in flight per lane
 constexpr int kPoolLdsDoubles = 1024;  // 8 KB: row-group partial sums (fp32), token-mean slices (fp64), drift marks
 
 // Device-scope (all XCDs) store of a value that another workgroup of the same launch will read
@@ -67,14 +68,26 @@ __device__ __forceinline__ void token_mean_workgroup(const float *src, int N, in
   const int per = (Nb + SL - 1) / SL;
   const int i0 = sl * per, i1 = min(Nb, i0 + per);
   double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
-#pragma unroll 8
-  for (int i = i0; i < i1; ++i) {
-    const float4 m = *reinterpret_cast<const float4 *>(src + (size_t)i * D + cg * 4);
-    const double n = (double)min(block, N - i * block);
-    a0 += (double)m.x * n;
-    a1 += (double)m.y * n;
-    a2 += (double)m.z * n;
-    a3 += (double)m.w * n;
+  // (the loads of kTokenMeanBatch blocks are issued before any is used: the kernel is bound by
+  // memory round trips; the order of the additions is the block order either way)
+  for (int ib = i0; ib < i1; ib += kTokenMeanBatch) {
+    float4 m[kTokenMeanBatch];
+#pragma unroll
+    for (int u = 0; u < kTokenMeanBatch; ++u) {
+      const int i = min(ib + u, i1 - 1);
+      m[u] = *reinterpret_cast<const float4 *>(src + (size_t)i * D + cg * 4);
+    }
+#pragma unroll
+    for (int u = 0; u < kTokenMeanBatch; ++u) {
+      const int i = ib + u;
+      if (i < i1) {
+        const double n = (double)min(block, N - i * block);
+        a0 += (double)m[u].x * n;
+        a1 += (double)m[u].y * n;
+        a2 += (double)m[u].z * n;
+        a3 += (double)m[u].w * n;
+      }
+    }
   }
   part[sl * D + cg * 4 + 0] = a0;
   part[sl * D + cg * 4 + 1] = a1;
