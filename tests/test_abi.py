@@ -98,6 +98,26 @@ def test_host_validation_rejects_bad_calls_without_a_gpu(lib):
                                None, None, None) == -1
 
 
+def test_pool_drift_validation_without_a_gpu(lib):
+    from paper_2605_14513_amd.binding import HeartShape
+
+    s = HeartShape()
+    s.B, s.H, s.N, s.D, s.block = 2, 40, 1000, 128, 128
+    for arr in (s.q_stride, s.k_stride, s.v_stride, s.o_stride):
+        arr[0], arr[1], arr[2] = 40 * 1000 * 128, 1000 * 128, 128
+    f = ctypes.c_void_p(0x10000)
+    args = lambda ws, nbytes, hi=0.8: (ctypes.byref(s), f, f, f, f, f, f, f, f, f, f, 0.4, hi, 1, f, f, ws, nbytes, None)
+    assert lib.heart_pool_drift_workspace_bytes(2, 40) == 2 * 4  # one ticket per batch item
+    assert lib.heart_pool_drift_workspace_bytes(0, 40) == 0
+    assert lib.heart_pool_drift(*args(None, 8)) == -1                     # no workspace
+    assert lib.heart_pool_drift(*args(f, 4)) == -1                        # too small
+    assert b"workspace" in lib.heart_last_error()
+    assert lib.heart_pool_drift(*args(ctypes.c_void_p(0x10002), 8)) == -2  # misaligned
+    assert lib.heart_pool_drift(*args(f, 8, hi=0.1)) == -1                # gate_lo > gate_hi
+    s.H = 5000
+    assert lib.heart_pool_drift(*args(f, 1 << 20)) == -2                  # more heads than the drift stage holds
+
+
 def test_estimator_validation_without_a_gpu(lib):
     """heart_scores_antidiag checks shape, stride relation, pointers, alignment and workspace
     size on the host; the pointers below are never dereferenced."""
