@@ -107,12 +107,27 @@ __device__ __forceinline__ void drift_workgroup(
   }
   __syncthreads();
   if (commit) {
-    for (int e = threadIdx.x; e < H * D; e += blockDim.x) {
-      int h = e / D;
-      if (fin[h]) {
-        size_t o = (size_t)b * H * D + e;
-        qanchor[o] = cur(qmean + o);
-        kanchor[o] = cur(kmean + o);
+    // (a lane loads its elements of a batch of passes before it stores any: the loads are
+    // independent round trips, the stores conditional on the head's decision)
+    constexpr int kBatch = 4;
+    const int n = H * D;
+    for (int e0 = threadIdx.x; e0 < n; e0 += kBatch * blockDim.x) {
+      float qv[kBatch], kv[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int e = min(e0 + u * (int)blockDim.x, n - 1);
+        const size_t o = (size_t)b * n + e;
+        qv[u] = cur(qmean + o);
+        kv[u] = cur(kmean + o);
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int e = e0 + u * (int)blockDim.x;
+        if (e < n && fin[e / D]) {
+          const size_t o = (size_t)b * n + e;
+          qanchor[o] = qv[u];
+          kanchor[o] = kv[u];
+        }
       }
     }
     for (int h = threadIdx.x; h < H; h += blockDim.x)

@@ -14,7 +14,7 @@
 //   rows in fp32 in row order, the 256/(D/8) row groups are combined through LDS
 //   in a fixed order (no atomics on data: results are reproducible), and the block mean
 //   is written once.
-// Token means (token_mean_workgroup): one workgroup of 256 lanes per (tensor, b, h) sums
+// Token means (token_mean_workgroup): one workgroup of 1024 lanes per (tensor, b, h) sums
 //   block_mean * n_block over the blocks in fp64 in a fixed order and divides by N
 //   (the mean of block means would be wrong when the last block is short).
 //   heart_pool_qk runs it as a second small kernel (pool_token_mean_kernel).
@@ -38,9 +38,10 @@ namespace heart {
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-constexpr int kPoolThreads = 256;
-constexpr int kTokenMeanBatch = 16;  // block means in flight per lane
-constexpr int kPoolLdsDoubles = 1024;  // 8 KB: row-group partial sums (fp32), token-mean slices (fp64), drift marks
+constexpr int kPoolThreads = 256;       // pooling pass: lanes per workgroup
+constexpr int kMeanThreads = 1024;      // token means (and the drift stage behind them): lanes per workgroup
+constexpr int kTokenMeanBatch = 8;      // block means in flight per lane
+constexpr int kMeanLdsDoubles = kMeanThreads * 4;  // 32 KB: token-mean slices (fp64); reused for the drift marks
 
 // Device-scope (all XCDs) store of a value that another workgroup of the same launch will read
 // (with a device-scope load): coherent across the L2 caches of the XCDs without a cache-wide
@@ -53,17 +54,18 @@ __device__ __forceinline__ void store_device_scope(float *p, float v) {
 __device__ __forceinline__ void wait_for_own_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // Token mean of one (tensor, b, h): src = its block means [Nb][D], dst = [D].  Lanes are
-// arranged as D/4 column groups (float4 each) times 256/(D/4) block slices; each slice adds
+// arranged as D/4 column groups (float4 each) times 1024/(D/4) block slices; each slice adds
 // its blocks in increasing block order in fp64, slices are combined in slice order.  Called
-// by a whole workgroup of 256 lanes (contains a barrier); part: LDS, kPoolLdsDoubles doubles.
+// by a whole workgroup of kMeanThreads lanes (contains a barrier); part: LDS, kMeanLdsDoubles
+// doubles.
 // kAcross: dst is read by another workgroup of this launch (device-scope stores); the
 // arithmetic is the same either way.
 template <int D, bool kAcross>
 __device__ __forceinline__ void token_mean_workgroup(const float *src, int N, int block, int Nb,
                                                      float *dst, double *part) {
   constexpr int CG = D / 4;             // column groups
-  constexpr int SL = kPoolThreads / CG; // slices over the blocks
-  static_assert(SL * D <= kPoolLdsDoubles, "LDS of the token mean");
+  constexpr int SL = kMeanThreads / CG; // slices over the blocks
+  static_assert(SL * D <= kMeanLdsDoubles, "LDS of the token mean");
   const int cg = threadIdx.x % CG, sl = threadIdx.x / CG;
   const int per = (Nb + SL - 1) / SL;
   const int i0 = sl * per, i1 = min(Nb, i0 + per);
@@ -183,12 +185,12 @@ __global__ __launch_bounds__(kPoolThreads) void pool_blocks_kernel(
 
 // One workgroup per (tensor, b, h).
 template <int D>
-__global__ __launch_bounds__(kPoolThreads) void pool_token_mean_kernel(const float *__restrict__ qblk,
+__global__ __launch_bounds__(kMeanThreads) void pool_token_mean_kernel(const float *__restrict__ qblk,
                                                                        const float *__restrict__ kblk,
                                                                        int N, int block, int Nb,
                                                                        float *__restrict__ qmean,
                                                                        float *__restrict__ kmean) {
-  __shared__ double part[kPoolLdsDoubles];
+  __shared__ double part[kMeanLdsDoubles];
   const int which = blockIdx.x & 1;
   const long long bh = blockIdx.x >> 1;
   token_mean_workgroup<D, false>((which ? kblk : qblk) + (size_t)bh * Nb * D, N, block, Nb,
@@ -200,10 +202,10 @@ __global__ __launch_bounds__(kPoolThreads) void pool_token_mean_kernel(const flo
 // acknowledged (wait, then barrier, then the atomic of one lane); the workgroup that draws the
 // last ticket of its batch item then reads every token mean with device-scope loads.
 template <int D>
-__global__ __launch_bounds__(kPoolThreads) void token_mean_drift_kernel(
+__global__ __launch_bounds__(kMeanThreads) void token_mean_drift_kernel(
     const float *__restrict__ qblk, const float *__restrict__ kblk, int H, int N, int block, int Nb,
     float *qmean, float *kmean, PoolDriftArgs fa) {
-  __shared__ double lds[kPoolLdsDoubles];
+  __shared__ double lds[kMeanLdsDoubles];
   __shared__ int s_last;
   const int which = blockIdx.x & 1;
   const long long bh = blockIdx.x >> 1;
@@ -231,17 +233,17 @@ static int launch_pool_t(const heart_shape &s, const uint16_t *qp, const uint16_
   const int Nb = (s.N + s.block - 1) / s.block;
   const long long nwg = 2LL * s.B * s.H * Nb;
   if (nwg > 0x7fffffffLL) return fail(HEART_EUNSUPPORTED, "heart_pool_qk: grid too large");
-  const dim3 grid((unsigned)nwg), blk(kPoolThreads), grid2((unsigned)(2 * s.B * s.H));
+  const dim3 grid((unsigned)nwg), blk(kPoolThreads), grid2((unsigned)(2 * s.B * s.H)), blk2(kMeanThreads);
   hipLaunchKernelGGL(pool_blocks_kernel<D>, grid, blk, 0, st, qp, kp, s.q_stride[0], s.q_stride[1],
                      s.q_stride[2], s.k_stride[0], s.k_stride[1], s.k_stride[2], s.H, s.N, s.block,
                      Nb, qblk, kblk);
   if (int rc = check_launch("pool_blocks_kernel")) return rc;
   if (fused) {
-    hipLaunchKernelGGL(token_mean_drift_kernel<D>, grid2, blk, 0, st, qblk, kblk, s.H, s.N, s.block,
+    hipLaunchKernelGGL(token_mean_drift_kernel<D>, grid2, blk2, 0, st, qblk, kblk, s.H, s.N, s.block,
                        Nb, qmean, kmean, *fused);
     return check_launch("token_mean_drift_kernel");
   }
-  hipLaunchKernelGGL(pool_token_mean_kernel<D>, grid2, blk, 0, st, qblk, kblk, s.N, s.block, Nb,
+  hipLaunchKernelGGL(pool_token_mean_kernel<D>, grid2, blk2, 0, st, qblk, kblk, s.N, s.block, Nb,
                      qmean, kmean);
   return check_launch("pool_token_mean_kernel");
 }
