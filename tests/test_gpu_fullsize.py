@@ -33,16 +33,18 @@ def heart():
     return pkg
 
 
-def attn_sample_check(name, out, st, idx, cnt, cfg, heads, qblocks, rows_ok=None):
-    """|out - oracle.attn| <= 2e-2 on the sampled query blocks of the sampled heads; rows_ok
-    [B,H,Nb] optionally excludes query blocks whose lists differ from the oracle's."""
+def attn_sample_check(name, out, st, idx, cnt, cfg, heads, qblocks, rows_ok=None, lse=None):
+    """|out - oracle.attn| <= 2e-2 (and, if given, |lse - oracle's| <= 2e-2) on the sampled query
+    blocks of the sampled heads; rows_ok [B,H,Nb] optionally excludes query blocks whose lists
+    differ from the oracle's."""
     blk, N = cfg.block, cfg.N
     worst = 0.0
     for h in heads:
         sub = lambda x: np.ascontiguousarray(u16(x)[:, h:h + 1])
-        want = oracle.attn(sub(st.q), sub(st.k), sub(st.v), blk, np.ascontiguousarray(idx[:, h:h + 1]),
-                           np.ascontiguousarray(cnt[:, h:h + 1]), qblocks=qblocks)
+        want, wlse = oracle.attn(sub(st.q), sub(st.k), sub(st.v), blk, np.ascontiguousarray(idx[:, h:h + 1]),
+                                 np.ascontiguousarray(cnt[:, h:h + 1]), qblocks=qblocks, want_lse=True)
         got = out[:, h:h + 1].float().cpu().numpy().astype(np.float64)
+        glse = None if lse is None else lse[:, h:h + 1].cpu().numpy().astype(np.float64)
         for i in qblocks:
             if rows_ok is not None and not rows_ok[:, h, i].all():
                 continue
@@ -50,6 +52,9 @@ def attn_sample_check(name, out, st, idx, cnt, cfg, heads, qblocks, rows_ok=None
             err = np.abs(got[:, :, n0:n1] - want[:, :, n0:n1]).max()
             worst = max(worst, err)
             assert err <= ATTN_ATOL, f"{name} head {h} q-block {i}: max abs err {err:.4f}"
+            if glse is not None:
+                lerr = np.abs(glse[:, :, n0:n1] - wlse[:, :, n0:n1]).max()
+                assert lerr <= ATTN_ATOL, f"{name} head {h} q-block {i}: log-sum-exp off by {lerr:.4f}"
     return worst
 
 
@@ -113,19 +118,22 @@ def test_full_size_path_against_oracle(heart, name):
     qblocks = sample_query_blocks(rng, Nb, nt, 32)
     for flags in (0, heart.HEART_ATTN_FOLD_SCALE):
         ws = torch.full((heart.heart_attn_workspace_bytes(q0, blk) // 4,), -1, dtype=torch.int32, device="cuda")
-        out = heart.heart_block_sparse_attn(q0, k0, v0, blk, np_gpu(oi), np_gpu(oc), workspace=ws, flags=flags)
+        lse = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+        out = heart.heart_block_sparse_attn(q0, k0, v0, blk, np_gpu(oi), np_gpu(oc), workspace=ws, flags=flags,
+                                            lse=lse)
         torch.cuda.synchronize()
         check_attn_plan(ws.cpu().numpy(), oc, Nb)
-        worst = attn_sample_check(name, out, st0, oi, oc, cfg, heads, qblocks)
+        worst = attn_sample_check(name, out, st0, oi, oc, cfg, heads, qblocks, lse=lse)
         print(f"[{name}] attention (flags {flags}) ok on heads {heads}, {len(qblocks)} query blocks each, "
               f"worst err {worst:.4f}", flush=True)
 
 
-def test_chained_full_size_steps_match_oracle(heart):
-    """Headline workload, the GPU path on its own intermediates (pool -> drift -> mask -> attention),
-    steps 0 and 1 of the schedule with carried TMR state: decisions equal the oracle's, masks equal
-    up to threshold rows, attention within tolerance on 32 sampled query blocks of 4 heads."""
-    name = "wan14b_480p"
+@pytest.mark.parametrize("name", FULL)
+def test_chained_full_size_steps_match_oracle(heart, name):
+    """Every full-size workload, the GPU path on its own intermediates in the calls the benchmark
+    times (pool + drift -> mask -> attention with a launch plan), steps 0 and 1 of the schedule with
+    carried TMR state: decisions equal the oracle's, masks equal up to threshold rows, attention
+    within tolerance on 32 sampled query blocks of 4 heads."""
     g = make_generator(name)
     cfg = g.cfg
     B, H, N, D, Nb, blk, nt = cfg.B, cfg.H, cfg.N, cfg.D, cfg.Nb, cfg.block, cfg.n_text_blocks
@@ -168,5 +176,5 @@ def test_chained_full_size_steps_match_oracle(heart):
         worst = attn_sample_check(name, out, st, chain.idx, chain.cnt, cfg, heads, qblocks, rows_ok=same)
         print(f"[{name}] chained step {s}: refreshed {orf.mean():.2f}, {int((~same).sum())} threshold rows, "
               f"attention worst err {worst:.4f}", flush=True)
-        if s == 1:
+        if s == 1 and cfg.schedule == "jumps":
             assert 0.3 <= orf.mean() <= 0.7, "the schedule keeps the refreshed share inside 30-70 %"
