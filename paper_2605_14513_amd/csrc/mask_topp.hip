@@ -192,12 +192,35 @@ __global__ __launch_bounds__(64 * kWaves, 4) void mask_topp_kernel(
       const unsigned long long T =
           tau_h > 0.f ? (unsigned long long)floorf(tau_h * 16777216.0f) : 0ull;
       const uint32_t need = (uint32_t)((T * (unsigned long long)U + 16777215ull) >> 24);
-      // the same bitwise search as in the general path, with the count of undecided scores
-      // kept incrementally: n_v = #(scores >= v), n_top = #(scores >= top)
-      uint32_t v = need == 0 ? 0x7fffffffu : 0u;
-      uint32_t n_v = 32 * EPL, n_top = 0;
+      // The same bitwise search as in the general path, shortened at the top: a score that
+      // carries mass is at least 2^-30, so mass(>= 2^-31) is the whole row (>= need) and bits
+      // 30..28 of the threshold are known (011); the exponent bits 27..23 are probed on masses
+      // alone (a binade holds many scores, the early exit below never fires there); from bit 22
+      // on the count of undecided scores is kept incrementally: n_v = #(scores >= v),
+      // n_top = #(scores >= top).
+      uint32_t v = need == 0 ? 0x7fffffffu : 0x30000000u;
       bool active = need != 0;
-      for (int bit = 30; bit >= 0; --bit) {
+      for (int bit = 27; bit >= 23; --bit) {
+        if (!__any(active)) break;
+        const uint32_t cand = v | (1u << bit);
+        uint32_t s = 0;
+#pragma unroll
+        for (int c = 0; c < EPL; ++c) s += e[c] >= cand ? u[c] : 0u;
+        s = half_sum_u32(s);
+        if (active && s >= need) v = cand;
+      }
+      uint32_t n_v = 0, n_top = 0;
+      {
+        const uint32_t top = v + (1u << 23);
+#pragma unroll
+        for (int c = 0; c < EPL; ++c) {
+          n_v += e[c] >= v ? 1u : 0u;
+          n_top += e[c] >= top ? 1u : 0u;
+        }
+        n_v = half_sum_u32(n_v);
+        n_top = half_sum_u32(n_top);
+      }
+      for (int bit = 22; bit >= 0; --bit) {
         if (!__any(active)) break;
         const uint32_t cand = v | (1u << bit);
         uint32_t s = 0, cn = 0;
@@ -363,8 +386,10 @@ __global__ __launch_bounds__(64 * kWaves, 4) void mask_topp_kernel(
       // [v, v + 2^(bit+1)) are undecided.  As soon as a single score is undecided it IS
       // v* (keeping it reaches the mass, dropping it does not), so the loop stops early:
       // typically after about a dozen steps instead of 31.  need == 0 keeps nothing here.
-      uint32_t v = need == 0 ? 0x7fffffffu : 0u;
-      for (int bit = 30; bit >= 0 && need != 0; --bit) {
+      // (a score that carries mass is at least 2^-30 and none exceeds 1, so bits 30..28 of the
+      // threshold are known: 011)
+      uint32_t v = need == 0 ? 0x7fffffffu : 0x30000000u;
+      for (int bit = 27; bit >= 0 && need != 0; --bit) {
         const uint32_t cand = v | (1u << bit);
         unsigned long long s = 0;
 #pragma unroll
