@@ -16,6 +16,7 @@ the CPU oracle's rate on a bounded sample are reported beside it.
 from __future__ import annotations
 
 import argparse
+import glob
 import json
 import os
 import sys
@@ -38,6 +39,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="wan14b_480p")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-power-probe", action="store_true",
+                    help="skip the 1.5 s of untimed attention launches under which board power and clock are read")
     ap.add_argument("--gate", default="0.4,0.8", help="layer gate lo,hi (0,1 disables)")
     ap.add_argument("--unfused", action="store_true",
                     help="call heart_pool_qk and heart_drift separately (three launches) instead of "
@@ -151,6 +154,68 @@ def measured_ceilings(heart, torch, q0, k0):
     out["hbm_read_gbs"] = best
     del src, dst
     return out
+
+
+def power_probe(torch, launch, seconds=1.5):
+    """Board power and shader clock while `launch` (one attention call) is repeated for about
+    `seconds`: read from the amdgpu driver's sysfs files of the one GPU of the box (hwmon power
+    sensor and cap in microwatts, current level of pp_dpm_sclk), sampled from the host every
+    0.1 s while the queued launches run; the first 0.7 s (the sensor's settling time) are dropped.
+    Extra information, outside every timed region; None where the files cannot be read."""
+    import numpy as np
+
+    def first_readable(patterns):
+        for pat in patterns:
+            for path in sorted(glob.glob(pat)):
+                try:
+                    with open(path) as f:
+                        f.read()
+                    return path
+                except OSError:
+                    pass
+        return None
+    hw = "/sys/class/drm/card*/device/hwmon/hwmon*/"
+    p_power = first_readable([hw + "power1_average", hw + "power1_input"])
+    p_cap = first_readable([hw + "power1_cap"])
+    p_sclk = first_readable(["/sys/class/drm/card*/device/pp_dpm_sclk"])
+    if p_power is None:
+        return None
+    def read(path):
+        with open(path) as f:
+            return f.read()
+    try:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        launch()
+        e1.record()
+        torch.cuda.synchronize()
+        n = max(1, int(seconds / (e0.elapsed_time(e1) * 1e-3)))
+        idle_w = int(read(p_power)) / 1e6
+        t0 = time.perf_counter()
+        for _ in range(n):
+            launch()
+        watts, mhz = [], []
+        while not torch.cuda.current_stream().query() and time.perf_counter() - t0 < 4 * seconds:
+            if time.perf_counter() - t0 >= 0.7:
+                watts.append(int(read(p_power)) / 1e6)
+                if p_sclk:
+                    cur = [ln for ln in read(p_sclk).splitlines() if ln.rstrip().endswith("*")]
+                    if cur:
+                        mhz.append(float(cur[0].split(":")[1].lower().replace("mhz", "").replace("*", "")))
+            time.sleep(0.1)
+        torch.cuda.synchronize()
+        if not watts:
+            return None
+        return {"launches": n, "seconds": time.perf_counter() - t0,
+                "board_power_w": float(np.mean(watts)), "board_power_w_max": float(np.max(watts)),
+                "board_power_cap_w": int(read(p_cap)) / 1e6 if p_cap else None,
+                "board_power_before_w": idle_w,
+                "shader_clock_mhz": float(np.mean(mhz)) if mhz else None,
+                "samples": len(watts), "source": "amdgpu sysfs (hwmon power sensor, pp_dpm_sclk)"}
+    except (OSError, ValueError, IndexError) as e:
+        print(f"[bench] power probe skipped: {e}", file=sys.stderr, flush=True)
+        return None
 
 
 def policy_sweep(args, heart, torch, g, steps_in, tau, delta):
@@ -527,6 +592,12 @@ def main():
     other_ms = float(np.mean([ev_o[i].elapsed_time(ev_o[i + 1]) for i in range(K)]))
     other_tflops = flops[-1] / (other_ms * 1e-3) / 1e12
 
+    # ---- board power and clock under the attention kernel (default path, same lists) ----
+    power = None
+    if not args.no_power_probe:
+        power = power_probe(torch, lambda: heart.heart_block_sparse_attn(
+            *steps_in[(K - 1) % S], blk, kidx, kcnt, out=out, workspace=attn_ws, flags=flags_main))
+
     # ---- the same schedule with the layer gate off (0 / 1), for the headline workload ----
     gate_off = None
     if (gate_lo, gate_hi) != (0.0, 1.0):
@@ -654,6 +725,9 @@ def main():
             "measured_mfma_only_tflops": {"zero_operands": ceil["zero_operands"],
                                           "workload_operands": ceil["workload_operands"]},
             "frac_of_measured_workload_operands": attn_tflops / ceil["workload_operands"],
+            # board power against its cap and the shader clock while this kernel runs back to
+            # back (the published peak is quoted at 2.4 GHz)
+            "power_probe": power,
         },
         "roofline_hbm_kernels": {
             "heart_pool_qk": {"bound": "hbm", "achieved": pool_bytes / (pool_ms * 1e-3) / 1e9,
