@@ -234,7 +234,9 @@ int heart_block_sparse_attn_flags(const heart_shape *shape, const void *q_bf16,
  * HEART_ATTN_STATIC_PLAN_BYTES, i.e. B*H*(Nb+2) + 24 <= 262144, and returns HEART_EUNSUPPORTED
  * beyond that.  Every call on a GPU shares that GPU's array (each call rebuilds the plan, so
  * nothing carries over from the previous one): calls that overlap on one GPU -- different
- * streams, or different host threads -- race; keep them stream-ordered.
+ * streams, or different host threads -- race; keep them stream-ordered.  The first call on a
+ * device looks up the array's device address and raises the kernels' LDS limit (two runtime
+ * queries, no allocation): make that call once before a stream capture begins.
  */
 #define HEART_ATTN_STATIC_PLAN_BYTES (1u << 20)
 int heart_block_sparse_attn_static(const heart_shape *shape, const void *q_bf16,
