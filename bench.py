@@ -39,6 +39,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="wan14b_480p")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fp64-scores", action="store_true",
+                    help="score stage of the mask kernel on the fp64 matrix cores also for long rows "
+                         "(default: 8-bit slices on the int8 matrix cores above 256 key blocks per row)")
     ap.add_argument("--no-power-probe", action="store_true",
                     help="skip the 1.5 s of untimed attention launches under which board power and clock are read")
     ap.add_argument("--gate", default="0.4,0.8", help="layer gate lo,hi (0,1 disables)")
@@ -494,6 +497,11 @@ def main():
     out = torch.empty_like(steps_in[0][0])
     attn_ws = torch.empty(heart.heart_workspace_bytes(B, H, Nb, D), dtype=torch.uint8, device=dev)
     tickets = torch.zeros(heart.heart_pool_drift_workspace_bytes(B, H), dtype=torch.uint8, device=dev)
+    # heart_mask_topp_ws (score stage on 8-bit slices: one launch more, pays for long rows)
+    from paper_2605_14513_amd.tmr import SLICED_SCORES_MIN_NB
+    topp_ws = None
+    if Nb > SLICED_SCORES_MIN_NB and not args.fp64_scores:
+        topp_ws = torch.empty(heart.heart_mask_topp_workspace_bytes(B, H, Nb, D), dtype=torch.uint8, device=dev)
     flags_main = heart.HEART_ATTN_FOLD_SCALE if args.fold_scale else 0
     flags_other = 0 if args.fold_scale else heart.HEART_ATTN_FOLD_SCALE
     path_name = {0: "fp32_scale (default)", heart.HEART_ATTN_FOLD_SCALE: "fold_scale"}
@@ -518,7 +526,8 @@ def main():
             if ev and inner: ev[1].record()
         if ev and inner: ev[2].record()
         heart.heart_mask_topp(qblk, kblk, tau, refresh=refresh, n_always_kv_blocks=nt,
-                              n_dense_q_blocks=nt, mask=mask, kept_idx=kidx, kept_count=kcnt)
+                              n_dense_q_blocks=nt, mask=mask, kept_idx=kidx, kept_count=kcnt,
+                              workspace=topp_ws)
         if ev: ev[3].record()
         heart.heart_block_sparse_attn(q, k, v, blk, kidx, kcnt, out=out, workspace=attn_ws, flags=flags)
         if ev: ev[4].record()
@@ -694,6 +703,7 @@ def main():
         "launch_overhead": launch,
         # (heart_pool_drift: "pool_qk" covers its two launches and "drift" is only an event gap)
         "token_means_and_drift_share_a_launch": not args.unfused,
+        "mask_score_stage": "int8 slices (heart_mask_topp_ws)" if topp_ws is not None else "fp64",
         "kernels_us": {"pool_qk": pool_ms * 1e3, "drift": drift_ms * 1e3,
                        "mask_topp": mask_ms * 1e3, "block_sparse_attn": attn_ms * 1e3},
         "attn_kept_tflops": attn_tflops,

@@ -155,6 +155,27 @@ int heart_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float 
                     void *stream);
 
 /*
+ * heart_mask_topp with a workspace: for D = 64 or 128 (and no scores_in) the dot products of
+ * the score stage then run on the int8 matrix cores, which are several times faster than the
+ * fp64 ones.  A first small launch writes every block mean of the refreshed heads into the
+ * workspace as an exponent and four signed 8-bit slices (the mean rounded to 31 bits below
+ * the power of two above its block's largest entry); products of slices and their sums over
+ * d are exact integers, and the slice pairs that matter are put together in fp64.  The
+ * logits differ from the exact dot products of the fp32 block means by less than 1e-6 of
+ * the product of the two blocks' largest entries, like those of the fp64 path they stay far
+ * inside the 1e-5 budget of the scores; everything after the logits is the same code.
+ * workspace: DEVICE, heart_mask_topp_workspace_bytes(B, H, Nb, D) bytes, 16-byte aligned,
+ * contents irrelevant on entry and undefined on return; calls that share it must be
+ * stream-ordered.  NULL workspace, scores_in given, or another D: exactly heart_mask_topp.
+ */
+size_t heart_mask_topp_workspace_bytes(int B, int H, int Nb, int D);
+int heart_mask_topp_ws(int B, int H, int Nb, int D, const float *qblk, const float *kblk,
+                       const float *scores_in, const float *tau, const unsigned char *refresh,
+                       int n_always_kv_blocks, int n_dense_q_blocks, int min_keep,
+                       unsigned char *mask, int *kept_idx, int *kept_count, float *scores_out,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * An alternative importance estimator for heart_mask_topp's scores_in argument: block
  * scores from strided antidiagonal sums of Q K^T.  The paper leaves importance ranking to
  * the sparse-attention backbone and names this family by its setting (antidiagonal scoring

@@ -16,6 +16,8 @@ from .binding import (  # noqa: F401
     heart_ebc_workspace_bytes,
     heart_last_error,
     heart_mask_topp,
+    heart_mask_topp_workspace_bytes,
+    heart_mask_topp_ws,
     heart_pool_drift,
     heart_pool_drift_workspace_bytes,
     heart_pool_qk,

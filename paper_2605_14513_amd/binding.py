@@ -57,6 +57,11 @@ def load_library() -> ctypes.CDLL:
     lib.heart_drift.argtypes = [ci, ci, ci, vp, vp, vp, vp, vp, vp, cf, cf, ci, vp, vp, vp]
     lib.heart_mask_topp.argtypes = [ci, ci, ci, ci, vp, vp, vp, vp, vp, ci, ci, ci, vp, vp, vp,
                                     vp, vp]
+    lib.heart_mask_topp_ws.argtypes = [ci, ci, ci, ci, vp, vp, vp, vp, vp, ci, ci, ci, vp, vp, vp,
+                                       vp, vp, ctypes.c_size_t, vp]
+    lib.heart_mask_topp_ws.restype = ci
+    lib.heart_mask_topp_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.heart_mask_topp_workspace_bytes.restype = ctypes.c_size_t
     lib.heart_block_sparse_attn.argtypes = [sp, vp, vp, vp, vp, vp, cf, vp, vp, vp,
                                             ctypes.c_size_t, vp]
     lib.heart_pool_drift.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, cf, cf, ci, vp, vp, vp,
@@ -239,8 +244,10 @@ def heart_pool_drift(q, k, block: int, qanchor, kanchor, has_anchor, delta, work
 
 def heart_mask_topp(qblk, kblk, tau, refresh=None, scores_in=None, n_always_kv_blocks: int = 0,
                     n_dense_q_blocks: int = 0, min_keep: int = 1, mask=None, kept_idx=None,
-                    kept_count=None, scores_out=None):
-    """Top-p block mask; writes mask/kept_idx/kept_count in place for refreshed heads."""
+                    kept_count=None, scores_out=None, workspace=None):
+    """Top-p block mask; writes mask/kept_idx/kept_count in place for refreshed heads.
+    workspace: a contiguous GPU tensor of at least heart_mask_topp_workspace_bytes(B, H, Nb, D)
+    bytes (heart_mask_topp_ws: score stage on the int8 matrix cores), or None."""
     lib = load_library()
     if scores_in is not None:
         B, H, Nb, _ = scores_in.shape
@@ -267,16 +274,33 @@ def heart_mask_topp(qblk, kblk, tau, refresh=None, scores_in=None, n_always_kv_b
         raise ValueError("refresh must be [B,H]")
     if scores_in is None and tuple(kblk.shape) != (B, H, Nb, D):
         raise ValueError("kblk must match qblk")
-    rc = lib.heart_mask_topp(B, H, Nb, D, _dev(qblk, torch.float32, "qblk"),
-                             _dev(kblk, torch.float32, "kblk"),
-                             _dev(scores_in, torch.float32, "scores_in"),
-                             _dev(tau, torch.float32, "tau"), _dev(refresh, torch.uint8, "refresh"),
-                             int(n_always_kv_blocks), int(n_dense_q_blocks), int(min_keep),
-                             _dev(mask, torch.uint8, "mask"), _dev(kept_idx, torch.int32, "kept_idx"),
-                             _dev(kept_count, torch.int32, "kept_count"),
-                             _dev(scores_out, torch.float32, "scores_out"), _stream())
-    _check("heart_mask_topp", rc)
+    args = (B, H, Nb, D, _dev(qblk, torch.float32, "qblk"), _dev(kblk, torch.float32, "kblk"),
+            _dev(scores_in, torch.float32, "scores_in"), _dev(tau, torch.float32, "tau"),
+            _dev(refresh, torch.uint8, "refresh"), int(n_always_kv_blocks), int(n_dense_q_blocks),
+            int(min_keep), _dev(mask, torch.uint8, "mask"), _dev(kept_idx, torch.int32, "kept_idx"),
+            _dev(kept_count, torch.int32, "kept_count"), _dev(scores_out, torch.float32, "scores_out"))
+    if workspace is None:
+        rc = lib.heart_mask_topp(*args, _stream())
+        _check("heart_mask_topp", rc)
+    else:
+        if not workspace.is_contiguous():
+            raise ValueError("workspace must be contiguous")
+        rc = lib.heart_mask_topp_ws(*args, ctypes.c_void_p(workspace.data_ptr()),
+                                    workspace.numel() * workspace.element_size(), _stream())
+        _check("heart_mask_topp_ws", rc)
     return mask, kept_idx, kept_count
+
+
+def heart_mask_topp_ws(qblk, kblk, tau, workspace, **kw):
+    """heart_mask_topp with a workspace (same keyword arguments)."""
+    if workspace is None:
+        raise ValueError("heart_mask_topp_ws needs a workspace")
+    return heart_mask_topp(qblk, kblk, tau, workspace=workspace, **kw)
+
+
+def heart_mask_topp_workspace_bytes(B: int, H: int, Nb: int, D: int) -> int:
+    """Bytes of workspace for heart_mask_topp(workspace=...)."""
+    return int(load_library().heart_mask_topp_workspace_bytes(int(B), int(H), int(Nb), int(D)))
 
 
 HEART_ATTN_FOLD_SCALE = 1  # flag of heart_block_sparse_attn_flags (include/heart.h)

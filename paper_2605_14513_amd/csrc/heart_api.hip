@@ -122,11 +122,12 @@ int heart_drift(int B, int H, int D, const float *qmean, const float *kmean, flo
                       gate_hi, commit, drift, refresh, (hipStream_t)stream);
 }
 
-int heart_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float *kblk,
-                    const float *scores_in, const float *tau, const unsigned char *refresh,
-                    int n_always_kv_blocks, int n_dense_q_blocks, int min_keep,
-                    unsigned char *mask, int *kept_idx, int *kept_count, float *scores_out,
-                    void *stream) {
+static int mask_topp_checked(int B, int H, int Nb, int D, const float *qblk, const float *kblk,
+                             const float *scores_in, const float *tau,
+                             const unsigned char *refresh, int n_always_kv_blocks,
+                             int n_dense_q_blocks, int min_keep, unsigned char *mask,
+                             int *kept_idx, int *kept_count, float *scores_out, void *workspace,
+                             size_t workspace_bytes, void *stream) {
   clear_error();
   if (B <= 0 || H <= 0 || Nb <= 0)
     return fail(HEART_EINVAL, "heart_mask_topp: B, H, Nb must be positive (got %d, %d, %d)", B,
@@ -149,9 +150,42 @@ int heart_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float 
     return fail(HEART_EINVAL, "heart_mask_topp: negative block-count argument");
   if ((long long)B * H * Nb > 0x7fffffffLL)
     return fail(HEART_EUNSUPPORTED, "heart_mask_topp: B*H*Nb exceeds the 1-D grid limit");
+  if (workspace) {
+    if (!aligned16(workspace))
+      return fail(HEART_EUNSUPPORTED, "heart_mask_topp_ws: workspace must be 16-byte aligned");
+    const size_t need = mask_topp_workspace_bytes(B, H, Nb, D);
+    if (!scores_in && workspace_bytes < need)
+      return fail(HEART_EINVAL, "heart_mask_topp_ws: workspace of %zu bytes, need %zu",
+                  workspace_bytes, need);
+  }
   return launch_mask_topp(B, H, Nb, D, qblk, kblk, scores_in, tau, refresh, n_always_kv_blocks,
                           n_dense_q_blocks, min_keep, mask, kept_idx, kept_count, scores_out,
-                          (hipStream_t)stream);
+                          workspace, (hipStream_t)stream);
+}
+
+int heart_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float *kblk,
+                    const float *scores_in, const float *tau, const unsigned char *refresh,
+                    int n_always_kv_blocks, int n_dense_q_blocks, int min_keep,
+                    unsigned char *mask, int *kept_idx, int *kept_count, float *scores_out,
+                    void *stream) {
+  return mask_topp_checked(B, H, Nb, D, qblk, kblk, scores_in, tau, refresh, n_always_kv_blocks,
+                           n_dense_q_blocks, min_keep, mask, kept_idx, kept_count, scores_out,
+                           nullptr, 0, stream);
+}
+
+int heart_mask_topp_ws(int B, int H, int Nb, int D, const float *qblk, const float *kblk,
+                       const float *scores_in, const float *tau, const unsigned char *refresh,
+                       int n_always_kv_blocks, int n_dense_q_blocks, int min_keep,
+                       unsigned char *mask, int *kept_idx, int *kept_count, float *scores_out,
+                       void *workspace, size_t workspace_bytes, void *stream) {
+  return mask_topp_checked(B, H, Nb, D, qblk, kblk, scores_in, tau, refresh, n_always_kv_blocks,
+                           n_dense_q_blocks, min_keep, mask, kept_idx, kept_count, scores_out,
+                           workspace, workspace_bytes, stream);
+}
+
+size_t heart_mask_topp_workspace_bytes(int B, int H, int Nb, int D) {
+  if (B <= 0 || H <= 0 || Nb <= 0 || D <= 0) return 0;
+  return mask_topp_workspace_bytes(B, H, Nb, D);
 }
 
 static int attn_checked(const heart_shape *shape, const void *q, const void *k, const void *v,

@@ -199,7 +199,9 @@ int launch_drift(int B, int H, int D, const float *qmean, const float *kmean, fl
 int launch_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float *kblk,
                      const float *scores_in, const float *tau, const unsigned char *refresh,
                      int n_always_kv, int n_dense_q, int min_keep, unsigned char *mask,
-                     int *kept_idx, int *kept_count, float *scores_out, hipStream_t st);
+                     int *kept_idx, int *kept_count, float *scores_out, void *workspace,
+                     hipStream_t st);
+size_t mask_topp_workspace_bytes(int B, int H, int Nb, int D);
 int launch_attn(const heart_shape &s, const void *q, const void *k, const void *v,
                 const int *kept_idx, const int *kept_count, float scale, unsigned flags, void *out,
                 float *lse, int *order, hipStream_t st);

@@ -13,6 +13,12 @@
 //            global memory, no LDS staging) and converts them to fp64 on the way in.
 //            The 16 query rows sit in LDS as fp64; the key blocks of the next tile are
 //            in flight while the current tile is multiplied.
+//            With a caller workspace (kInt8) the same dot products run on the int8 matrix
+//            cores instead, which are 6 times faster per tile than the fp64 ones: a small
+//            kernel first writes every block mean as an exponent and four signed 8-bit
+//            slices (slice_blocks_kernel), products of slices and their sums over d are
+//            exact integers (v_mfma_i32_16x16x64_i8), and the slice pairs are put together
+//            in fp64.
 //   Phase B  row softmax, fp32 with the accurate expf: half a wavefront per row (two rows at
 //            a time) when the scores are the kernel's own, one wavefront per row for scores
 //            passed in.
@@ -33,17 +39,75 @@ constexpr int kRows = 16;      // query-block rows per workgroup (one MFMA tile 
 constexpr int kMaxF4 = 8;      // float4 per lane and tile at D = 128 (D/16)
 constexpr int kWaves = 8;      // wavefronts per workgroup: two rows each per selection pass
 typedef __attribute__((ext_vector_type(4))) double f64x4_t;
+typedef __attribute__((ext_vector_type(4))) int i32x4_t;
+
+// ---- exact 8-bit slices of the block means ------------------------------------------------
+// A block mean x[D] (fp32) becomes an exponent E with |x_d| < 2^E for every d and the
+// integers m_d = round(x_d 2^(30-E)), |m_d| <= 2^30, each written as four signed bytes
+//   m = b0 2^24 + b1 2^16 + b2 2^8 + b3,   b1..b3 in [-128, 127], b0 in [-64, 64]
+// (balanced digits, so that every slice fits the int8 operands of the matrix cores).  The
+// rounding moves x_d by at most 2^(E-31), i.e. 2^-31 of the largest entry of its block: far
+// inside the 1e-5 budget of the scores (fp32 block means carry 2^-24 themselves).
+// Layout: slices [vector][slice t = 0 (b0) .. 3][D] bytes, exponents [vector]; vector =
+// (b*H + h) * Nb + block.  Not finite inputs give unspecified (but defined) slices.
+constexpr int kSliceThreads = 256;
+template <int D>
+__global__ __launch_bounds__(kSliceThreads) void slice_blocks_kernel(
+    long long n_vec, int Nb, const float *__restrict__ qblk, const float *__restrict__ kblk,
+    const unsigned char *__restrict__ refresh, signed char *__restrict__ qs,
+    signed char *__restrict__ ks, int *__restrict__ qe, int *__restrict__ ke) {
+  constexpr int LPV = D / 4;                   // lanes per vector (a float4 each)
+  constexpr int VPW = kSliceThreads / LPV;     // vectors per workgroup
+  const int lv = threadIdx.x % LPV;
+  const long long vid2 = (long long)blockIdx.x * VPW + threadIdx.x / LPV;  // over q then k
+  const bool is_k = vid2 >= n_vec;
+  const long long vid = is_k ? vid2 - n_vec : vid2;
+  // (lanes of a vector share one wavefront and take the same branch)
+  if (vid >= n_vec) return;
+  if (refresh && !refresh[vid / Nb]) return;  // reused head: its scores are not computed
+  const float4 x = reinterpret_cast<const float4 *>((is_k ? kblk : qblk) + vid * D)[lv];
+  float amax = fmaxf(fmaxf(fabsf(x.x), fabsf(x.y)), fmaxf(fabsf(x.z), fabsf(x.w)));
+#pragma unroll
+  for (int d = 1; d < LPV; d <<= 1) amax = fmaxf(amax, __shfl_xor(amax, d, 64));
+  // |x| < 2^E: E = biased exponent - 126 (zeros and denormals: the smallest normal binade)
+  const int be = (int)((__float_as_uint(amax) >> 23) & 0xffu);
+  const int E = (be > 0 ? be : 1) - 126;
+  const float lim = 1073741824.0f;  // 2^30
+  const float xs[4] = {x.x, x.y, x.z, x.w};
+  uint32_t word[4] = {0u, 0u, 0u, 0u};  // word[t]: slice t of this lane's four d
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float scaled = fminf(fmaxf(rintf(ldexpf(xs[e], 30 - E)), -lim), lim);
+    int m = (int)scaled;
+#pragma unroll
+    for (int t = 3; t >= 0; --t) {
+      const int bt = t > 0 ? (int)(signed char)(m & 0xff) : m;  // low byte, signed; the rest for b0
+      m = (m - bt) >> 8;
+      word[t] |= ((uint32_t)bt & 0xffu) << (8 * e);
+    }
+  }
+  uint32_t *dst = reinterpret_cast<uint32_t *>((is_k ? ks : qs) + vid * 4 * D);
+#pragma unroll
+  for (int t = 0; t < 4; ++t) dst[t * (D / 4) + lv] = word[t];
+  if (lv == 0) (is_k ? ke : qe)[vid] = E;
+}
 
 // CMAX: slots per lane; handles Nb <= 64 * CMAX.  NF4T: D / 16 when known at compile time
 // (4 or 8), else 0: with it the contraction loop is branch-free, so that the loads of the next
 // tile stay in flight under the matrix instructions of the current one.
-template <int CMAX, int NF4T>
+// kInt8: the score stage reads the slices written by slice_blocks_kernel (NF4T = 4 or 8 only).
+struct BlockSlices {
+  const signed char *qs, *ks;  // [B*H*Nb][4][D]
+  const int *qe, *ke;          // [B*H*Nb]
+};
+template <int CMAX, int NF4T, bool kInt8>
 __global__ __launch_bounds__(64 * kWaves, 4) void mask_topp_kernel(
     int H, int Nb, int D, const float *__restrict__ qblk, const float *__restrict__ kblk,
     const float *__restrict__ scores_in, const float *__restrict__ tau,
     const unsigned char *__restrict__ refresh, int n_always_kv, int n_dense_q, int min_keep,
     unsigned char *__restrict__ mask, int *__restrict__ kept_idx, int *__restrict__ kept_count,
-    float *__restrict__ scores_out) {
+    float *__restrict__ scores_out, BlockSlices sl) {
+  static_assert(!kInt8 || NF4T == 4 || NF4T == 8, "slices: D = 64 or 128");
   extern __shared__ __align__(16) unsigned char smem_raw[];
   constexpr int NBP = 64 * CMAX;
   float *sP = reinterpret_cast<float *>(smem_raw);  // [kRows][NBP] logits of the rows
@@ -58,7 +122,77 @@ __global__ __launch_bounds__(64 * kWaves, 4) void mask_topp_kernel(
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
-  if (!scores_in) {
+  if constexpr (kInt8) {
+    // ---- Phase A on the int8 matrix cores (launched only without scores_in) -------- -----------------------------------------
+    // v_mfma_i32_16x16x64_i8: A lane L = (row L%16, 16 bytes of k-group L/16), B lane L =
+    // (16 bytes of k-group L/16, column L%16), D lane L register r = (row 4*(L/16) + r,
+    // column L%16).  Both operands use the same assignment of d to (k-group, byte): group g
+    // holds d = 64 c + 16 g .. + 15 of chunk c.  Slice pairs (ta, tb) carry the weight
+    // 2^(48 - 8 (ta + tb)); pairs of equal weight share an accumulator, and the pairs with
+    // ta + tb > 3 (weights 2^16 and below against sums of up to 2^69: 2^-23 of the product of
+    // the two blocks' largest entries at worst) are left out.
+    constexpr int DD = 16 * NF4T, NC = DD / 64;
+    const int n16 = lane & 15, g = lane >> 4;
+    const size_t vec0 = (size_t)bh * Nb;
+    i32x4_t aq[4][NC];
+    {
+      const int qi = min(i0 + n16, Nb - 1);
+      const i32x4_t *qp = reinterpret_cast<const i32x4_t *>(sl.qs + (vec0 + qi) * 4 * DD);
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int c = 0; c < NC; ++c) aq[t][c] = qp[t * (DD / 16) + 4 * c + g];
+    }
+    int eq[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) eq[r] = sl.qe[vec0 + min(i0 + 4 * g + r, Nb - 1)];
+    // (columns past Nb read the last key block instead of branching; their logits are not
+    // stored)
+    auto load_tile = [&](i32x4_t (&dst)[4][NC], int &ek, int tile) {
+      const int j = min(tile * 16 + n16, Nb - 1);
+      const i32x4_t *kp = reinterpret_cast<const i32x4_t *>(sl.ks + (vec0 + j) * 4 * DD);
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int c = 0; c < NC; ++c) dst[t][c] = kp[t * (DD / 16) + 4 * c + g];
+      ek = sl.ke[vec0 + j];
+    };
+    const double inv_sqrt_d = 1.0 / sqrt((double)DD);
+    const int ntiles = (Nb + 15) / 16;
+    i32x4_t kc[4][NC], kn[4][NC];
+    int ekc = 0, ekn = 0;
+    if (wave < ntiles) load_tile(kc, ekc, wave);
+    for (int tile = wave; tile < ntiles; tile += kWaves) {
+      if (tile + kWaves < ntiles) load_tile(kn, ekn, tile + kWaves);
+      i32x4_t acc[4];
+#pragma unroll
+      for (int w = 0; w < 4; ++w) acc[w] = i32x4_t{0, 0, 0, 0};
+#pragma unroll
+      for (int c = 0; c < NC; ++c)
+#pragma unroll
+        for (int ta = 0; ta < 4; ++ta)
+#pragma unroll
+          for (int w = ta; w < 4; ++w)  // (accumulators in turn: few back-to-back dependent pairs)
+            acc[w] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aq[ta][c], kc[w - ta][c], acc[w], 0, 0, 0);
+      const int j = tile * 16 + n16;
+      if (j < Nb) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          // exact in fp64: every accumulator is below 2^24 in magnitude
+          const double v = (((double)acc[0][r] * 256.0 + (double)acc[1][r]) * 256.0 + (double)acc[2][r]) * 256.0 +
+                           (double)acc[3][r];
+          // v * 2^24 * 2^(Eq - 30) * 2^(Ek - 30)
+          sP[(4 * g + r) * NBP + j] = (float)(ldexp(v, eq[r] + ekc - 36) * inv_sqrt_d);
+        }
+      }
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int c = 0; c < NC; ++c) kc[t][c] = kn[t][c];
+      ekc = ekn;
+    }
+    __syncthreads();
+  } else if (!scores_in) {
     // ---- Phase A: logits -------------------------------------------------------
     // MFMA operand layout (16x16x4 fp64): A lane L = (row L%16, k L/16), B lane L =
     // (k L/16, column L%16), D lane L register r = (row L/16 + 4 r, column L%16).
@@ -475,50 +609,88 @@ __global__ __launch_bounds__(64 * kWaves, 4) void mask_topp_kernel(
   }
 }
 
-template <int CMAX, int NF4T>
+template <int CMAX, int NF4T, bool kInt8>
 static int launch_cmax_d(int B, int H, int Nb, int D, const float *qblk, const float *kblk,
                        const float *scores_in, const float *tau, const unsigned char *refresh,
                        int n_always_kv, int n_dense_q, int min_keep, unsigned char *mask,
-                       int *kept_idx, int *kept_count, float *scores_out, hipStream_t st) {
+                       int *kept_idx, int *kept_count, float *scores_out, const BlockSlices &sl,
+                       hipStream_t st) {
   int groups = (Nb + kRows - 1) / kRows;
-  size_t lds = scores_in ? 0 : (size_t)kRows * 64 * CMAX * 4 + (size_t)kRows * (D + 2) * 8;
+  // logits of the row group; the fp64 score stage also keeps its query rows there
+  size_t lds = scores_in ? 0 : (size_t)kRows * 64 * CMAX * 4 + (kInt8 ? 0 : (size_t)kRows * (D + 2) * 8);
   long long nwg = (long long)B * H * groups;
+  auto kern = mask_topp_kernel<CMAX, NF4T, kInt8>;
   if (lds > 64 * 1024) {
     const int dev = current_device();
     if (dev < 0) return fail(HEART_EHIP, "heart_mask_topp: cannot identify the current device");
     static DeviceFlags attr_set;  // per instantiation: the attribute is per function and device
-    if (hipError_t e = set_max_lds_once(attr_set, dev,
-                                        reinterpret_cast<const void *>(mask_topp_kernel<CMAX, NF4T>), 96 * 1024))
+    if (hipError_t e = set_max_lds_once(attr_set, dev, reinterpret_cast<const void *>(kern), 96 * 1024))
       return fail(HEART_EHIP, "hipFuncSetAttribute(mask kernel LDS): %s", hipGetErrorString(e));
   }
-  hipLaunchKernelGGL((mask_topp_kernel<CMAX, NF4T>), dim3((unsigned)nwg), dim3(64 * kWaves), lds, st, H,
-                     Nb, D, qblk, kblk, scores_in, tau, refresh, n_always_kv, n_dense_q, min_keep,
-                     mask, kept_idx, kept_count, scores_out);
+  hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(64 * kWaves), lds, st, H, Nb, D, qblk, kblk,
+                     scores_in, tau, refresh, n_always_kv, n_dense_q, min_keep, mask, kept_idx,
+                     kept_count, scores_out, sl);
   return check_launch("mask_topp_kernel");
+}
+
+template <int D>
+static int launch_slices(int B, int H, int Nb, const float *qblk, const float *kblk,
+                         const unsigned char *refresh, signed char *qs, signed char *ks, int *qe,
+                         int *ke, hipStream_t st) {
+  const long long n_vec = (long long)B * H * Nb;
+  constexpr int VPW = kSliceThreads / (D / 4);
+  const long long nwg = (2 * n_vec + VPW - 1) / VPW;
+  if (nwg > 0x7fffffffLL) return fail(HEART_EUNSUPPORTED, "heart_mask_topp: too many blocks to slice");
+  hipLaunchKernelGGL(slice_blocks_kernel<D>, dim3((unsigned)nwg), dim3(kSliceThreads), 0, st, n_vec, Nb,
+                     qblk, kblk, refresh, qs, ks, qe, ke);
+  return check_launch("slice_blocks_kernel");
+}
+
+size_t mask_topp_workspace_bytes(int B, int H, int Nb, int D) {
+  // slices of Q and K blocks (4 D bytes each) and their exponents
+  return (size_t)B * H * Nb * (2 * (size_t)4 * D + 2 * sizeof(int));
 }
 
 template <int CMAX>
 static int launch_cmax(int B, int H, int Nb, int D, const float *qblk, const float *kblk,
                        const float *scores_in, const float *tau, const unsigned char *refresh,
                        int n_always_kv, int n_dense_q, int min_keep, unsigned char *mask,
-                       int *kept_idx, int *kept_count, float *scores_out, hipStream_t st) {
+                       int *kept_idx, int *kept_count, float *scores_out, void *workspace,
+                       hipStream_t st) {
 #define HEART_TOPP_D_ARGS                                                                     \
   B, H, Nb, D, qblk, kblk, scores_in, tau, refresh, n_always_kv, n_dense_q, min_keep, mask,   \
-      kept_idx, kept_count, scores_out, st
+      kept_idx, kept_count, scores_out
+  BlockSlices none{nullptr, nullptr, nullptr, nullptr};
+  if (!scores_in && workspace && (D == 128 || D == 64)) {
+    // score stage on the int8 matrix cores: slices first (one small launch), then the kernel
+    const size_t n_vec = (size_t)B * H * Nb;
+    signed char *qs = static_cast<signed char *>(workspace);
+    signed char *ks = qs + n_vec * 4 * D;
+    int *qe = reinterpret_cast<int *>(ks + n_vec * 4 * D);
+    int *ke = qe + n_vec;
+    const BlockSlices sl{qs, ks, qe, ke};
+    if (D == 128) {
+      if (int rc = launch_slices<128>(B, H, Nb, qblk, kblk, refresh, qs, ks, qe, ke, st)) return rc;
+      return launch_cmax_d<CMAX, 8, true>(HEART_TOPP_D_ARGS, sl, st);
+    }
+    if (int rc = launch_slices<64>(B, H, Nb, qblk, kblk, refresh, qs, ks, qe, ke, st)) return rc;
+    return launch_cmax_d<CMAX, 4, true>(HEART_TOPP_D_ARGS, sl, st);
+  }
   // the head dimensions of the attention kernels get a contraction loop of their own
-  if (!scores_in && D == 128) return launch_cmax_d<CMAX, 8>(HEART_TOPP_D_ARGS);
-  if (!scores_in && D == 64) return launch_cmax_d<CMAX, 4>(HEART_TOPP_D_ARGS);
-  return launch_cmax_d<CMAX, 0>(HEART_TOPP_D_ARGS);
+  if (!scores_in && D == 128) return launch_cmax_d<CMAX, 8, false>(HEART_TOPP_D_ARGS, none, st);
+  if (!scores_in && D == 64) return launch_cmax_d<CMAX, 4, false>(HEART_TOPP_D_ARGS, none, st);
+  return launch_cmax_d<CMAX, 0, false>(HEART_TOPP_D_ARGS, none, st);
 #undef HEART_TOPP_D_ARGS
 }
 
 int launch_mask_topp(int B, int H, int Nb, int D, const float *qblk, const float *kblk,
                      const float *scores_in, const float *tau, const unsigned char *refresh,
                      int n_always_kv, int n_dense_q, int min_keep, unsigned char *mask,
-                     int *kept_idx, int *kept_count, float *scores_out, hipStream_t st) {
+                     int *kept_idx, int *kept_count, float *scores_out, void *workspace,
+                     hipStream_t st) {
 #define HEART_TOPP_ARGS                                                                       \
   B, H, Nb, D, qblk, kblk, scores_in, tau, refresh, n_always_kv, n_dense_q, min_keep, mask,   \
-      kept_idx, kept_count, scores_out, st
+      kept_idx, kept_count, scores_out, workspace, st
   // (lane slots in steps of 128 key blocks above 256: unused slots cost selection work)
   if (Nb <= 64) return launch_cmax<1>(HEART_TOPP_ARGS);
   if (Nb <= 256) return launch_cmax<4>(HEART_TOPP_ARGS);

@@ -98,6 +98,20 @@ def test_host_validation_rejects_bad_calls_without_a_gpu(lib):
                                None, None, None) == -1
 
 
+def test_mask_topp_workspace_validation_without_a_gpu(lib):
+    f = ctypes.c_void_p(0x10000)
+    need = 1 * 40 * 256 * (2 * 4 * 128 + 2 * 4)  # slices of Q and K blocks and their exponents
+    assert lib.heart_mask_topp_workspace_bytes(1, 40, 256, 128) == need
+    assert lib.heart_mask_topp_workspace_bytes(1, 0, 256, 128) == 0
+    args = lambda ws, nbytes: (1, 40, 256, 128, f, f, None, f, None, 0, 0, 1, f, f, f, None, ws, nbytes, None)
+    assert lib.heart_mask_topp_ws(*args(f, need - 1)) == -1                     # too small
+    assert b"workspace" in lib.heart_last_error()
+    assert lib.heart_mask_topp_ws(*args(ctypes.c_void_p(0x10008), need)) == -2  # misaligned
+    assert lib.heart_mask_topp_ws(1, 1, 2000, 128, f, f, None, f, None, 0, 0, 1, f, f, f, None, f,
+                                  1 << 30, None) == -2                           # the checks of heart_mask_topp
+    assert b"HEART_MAX_NB" in lib.heart_last_error()
+
+
 def test_pool_drift_validation_without_a_gpu(lib):
     from paper_2605_14513_amd.binding import HeartShape
 

@@ -102,6 +102,16 @@ def test_full_size_path_against_oracle(heart, name):
                           n_always_kv_blocks=nt, n_dense_q_blocks=nt)
     torch.cuda.synchronize()
     rel = assert_scores_close(gsc, osc, name)
+    # the score stage on 8-bit slices (heart_mask_topp_ws; what the benchmark runs for long rows)
+    tws = torch.empty(heart.heart_mask_topp_workspace_bytes(B, H, Nb, D), dtype=torch.uint8, device="cuda")
+    gsc2 = torch.empty_like(gsc)
+    heart.heart_mask_topp(np_gpu(oqb), np_gpu(okb), np_gpu(tau), scores_out=gsc2,
+                          n_always_kv_blocks=nt, n_dense_q_blocks=nt, workspace=tws)
+    torch.cuda.synchronize()
+    rel2 = assert_scores_close(gsc2, osc, name + " (sliced)")
+    print(f"[{name}] sliced score stage: max rel err {rel2:.2e}, "
+          f"{int((gsc2 != gsc).sum().item())} of {gsc.numel()} scores differ in bits from the fp64 stage", flush=True)
+    del tws, gsc2
     om, oi, oc = oracle.topp(osc, tau, n_always_kv=nt, n_dense_q=nt)
     gm, gi, gc = heart.heart_mask_topp(None, None, np_gpu(tau), scores_in=np_gpu(osc),
                                        n_always_kv_blocks=nt, n_dense_q_blocks=nt)
@@ -146,6 +156,11 @@ def test_chained_full_size_steps_match_oracle(heart, name):
     gcnt = torch.zeros((B, H, Nb), dtype=torch.int32, device=dev)
     ws = torch.empty(heart.heart_workspace_bytes(B, H, Nb, D), dtype=torch.uint8, device=dev)
     tickets = torch.zeros(heart.heart_pool_drift_workspace_bytes(B, H), dtype=torch.uint8, device=dev)
+    # (as in bench.py: long rows take the score stage on 8-bit slices)
+    from paper_2605_14513_amd.tmr import SLICED_SCORES_MIN_NB
+    tws = None
+    if Nb > SLICED_SCORES_MIN_NB:
+        tws = torch.empty(heart.heart_mask_topp_workspace_bytes(B, H, Nb, D), dtype=torch.uint8, device=dev)
     chain = OracleChain(cfg, g.tau, g.delta)
     gtau, gdelta = np_gpu(g.tau), np_gpu(g.delta)
     rng = np.random.default_rng(cfg.seed + 1)
@@ -158,7 +173,7 @@ def test_chained_full_size_steps_match_oracle(heart, name):
         # (the calls bench.py times: token means and drift share a launch)
         qblk, kblk, qmean, kmean, d, r = heart.heart_pool_drift(q, k, blk, gq, gk, gh, gdelta, tickets, 0.4, 0.8)
         heart.heart_mask_topp(qblk, kblk, gtau, refresh=r, n_always_kv_blocks=nt, n_dense_q_blocks=nt,
-                              mask=gmask, kept_idx=gidx, kept_count=gcnt)
+                              mask=gmask, kept_idx=gidx, kept_count=gcnt, workspace=tws)
         out = heart.heart_block_sparse_attn(q, k, v, blk, gidx, gcnt, workspace=ws)
         torch.cuda.synchronize()
         assert not tickets.any().item()

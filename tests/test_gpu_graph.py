@@ -21,7 +21,7 @@ from heart_testlib import (ATTN_ATOL, SCORE_RTOL, OracleChain, assert_masks_equa
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("estimator", ["pooled", "antidiag"])
+@pytest.mark.parametrize("estimator", ["pooled", "pooled_sliced", "antidiag"])
 def test_captured_step_replays_bit_exact(estimator):
     import paper_2605_14513_amd as heart
 
@@ -53,16 +53,20 @@ def test_captured_step_replays_bit_exact(estimator):
             scores=torch.zeros((B, H, Nb, Nb), **f32),
             ews=torch.empty(heart.heart_scores_antidiag_workspace_bytes(
                 torch.empty((B, H, N, D), dtype=torch.bfloat16, device=dev), blk, blk // 8),
-                dtype=torch.uint8, device=dev))
+                dtype=torch.uint8, device=dev),
+            # heart_mask_topp_ws: the score stage on 8-bit slices, one more launch in the graph
+            tws=(torch.empty(heart.heart_mask_topp_workspace_bytes(B, H, Nb, D), dtype=torch.uint8, device=dev)
+                 if estimator == "pooled_sliced" else None))
 
     def step(s):
         # pooling pass, then token means, drift and gate in one launch (its ticket counters return to zero
         # by themselves, which a replayed graph relies on)
         heart.heart_pool_drift(s["q"], s["k"], blk, s["qa"], s["ka"], s["has"], delta, s["tickets"], 0.4, 0.8,
                                True, s["qblk"], s["kblk"], s["qmean"], s["kmean"], s["drift"], s["refresh"])
-        if estimator == "pooled":
+        if estimator.startswith("pooled"):
             heart.heart_mask_topp(s["qblk"], s["kblk"], tau, refresh=s["refresh"], n_always_kv_blocks=nt,
-                                  n_dense_q_blocks=nt, mask=s["mask"], kept_idx=s["kidx"], kept_count=s["kcnt"])
+                                  n_dense_q_blocks=nt, mask=s["mask"], kept_idx=s["kidx"], kept_count=s["kcnt"],
+                                  workspace=s["tws"])
         else:
             heart.heart_scores_antidiag(s["q"], s["k"], blk, blk // 8, scores=s["scores"], workspace=s["ews"],
                                         refresh=s["refresh"])
@@ -117,7 +121,7 @@ def test_captured_step_replays_bit_exact(estimator):
         assert np.array_equal(cap["has"].cpu().numpy(), chain.has)
         fin = np.isfinite(od)
         assert np.allclose(cap["drift"].cpu().numpy()[fin], od[fin], rtol=1e-4, atol=1e-6)
-        if estimator == "pooled":
+        if estimator.startswith("pooled"):
             osc, tol = chain.scores, SCORE_RTOL
             shift = pooled_mean_score_shift(osc, cap["qblk"], cap["kblk"])
         else:

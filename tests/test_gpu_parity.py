@@ -213,21 +213,73 @@ def test_pool_drift_commit_off_and_validation(heart):
 
 
 # ------------------------------------------------------------------------------ P3
+def _topp_workspace(heart, shape, sliced):
+    """A workspace for heart_mask_topp (score stage on 8-bit slices of the block means), or None."""
+    if not sliced:
+        return None
+    B, H, Nb, D = shape
+    return torch.empty(heart.heart_mask_topp_workspace_bytes(B, H, Nb, D), dtype=torch.uint8, device="cuda")
+
+
+@pytest.mark.parametrize("sliced", [False, True])
 @pytest.mark.parametrize("name", SMALL)
-def test_scores_match_oracle(heart, name):
+def test_scores_match_oracle(heart, name, sliced):
     g, st = case(name)
     cfg = g.cfg
     qblk, _ = oracle.pool(u16(st.q), cfg.block)
     kblk, _ = oracle.pool(u16(st.k), cfg.block)
     want = oracle.scores(qblk, kblk)
     out = torch.empty(want.shape, dtype=torch.float32, device="cuda")
-    print(f"scores {name} Nb={cfg.Nb}", flush=True)
-    heart.heart_mask_topp(np_gpu(qblk), np_gpu(kblk), np_gpu(g.tau), scores_out=out)
+    print(f"scores {name} Nb={cfg.Nb} sliced={sliced}", flush=True)
+    heart.heart_mask_topp(np_gpu(qblk), np_gpu(kblk), np_gpu(g.tau), scores_out=out,
+                          workspace=_topp_workspace(heart, qblk.shape, sliced))
     torch.cuda.synchronize()
     assert_scores_close(out, want, name)
 
 
-def test_scores_large_logits_and_many_blocks(heart):
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("Nb", [1, 17, 100, 300, 600])
+def test_scores_from_slices_wide_dynamic_range(heart, D, Nb):
+    """The score stage on 8-bit slices: block means whose entries span many binades inside one
+    block and from block to block, zero blocks, denormal entries, a lone large entry, partial
+    refresh (reused heads are neither sliced nor written) -- scores against the oracle, and the
+    kept lists against the oracle's selection from the scores the kernel reports."""
+    rng = np.random.default_rng(7 * Nb + D)
+    B, H = 2, 3
+    mag = 2.0 ** rng.integers(-12, 3, size=(B, H, Nb, D))           # entry-wise binades
+    qblk = (rng.standard_normal((B, H, Nb, D)) * mag).astype(np.float32)
+    blockmag = 2.0 ** rng.integers(-6, 2, size=(B, H, Nb, 1))        # block-wise binades
+    kblk = (rng.standard_normal((B, H, Nb, D)) * blockmag).astype(np.float32)
+    kblk[0, 0, 0] = 0.0                                              # a zero block
+    qblk[0, 1, Nb // 2] = 0.0
+    kblk[1, 2, Nb - 1, : D // 2] = np.float32(1e-41)                 # denormal entries
+    kblk[1, 0, Nb // 3] = 0.0
+    kblk[1, 0, Nb // 3, 5] = 3.0                                     # a lone large entry
+    qblk[1, 0, :, 5] += 1.5
+    tau = np.array([0.9, 0.6, 0.97], np.float32)
+    want = oracle.scores(qblk, kblk)
+    ws = _topp_workspace(heart, qblk.shape, True)
+    out = torch.zeros(want.shape, dtype=torch.float32, device="cuda")
+    print(f"sliced scores Nb={Nb} D={D}", flush=True)
+    gm, gi, gc = heart.heart_mask_topp(np_gpu(qblk), np_gpu(kblk), np_gpu(tau), scores_out=out, workspace=ws)
+    torch.cuda.synchronize()
+    assert_scores_close(out, want, f"slices Nb={Nb} D={D}")
+    om, oi, oc = oracle.topp(out.cpu().numpy(), tau)
+    assert_lists_equal(gm, gi, gc, om, oi, oc, f"slices Nb={Nb} D={D}")
+    # partial refresh: the same call on poisoned outputs writes refreshed heads only, same bits
+    refresh = np.array([[1, 0, 1], [0, 1, 0]], np.uint8)
+    m2 = torch.full_like(gm, 7); i2 = torch.full_like(gi, -5); c2 = torch.full_like(gc, -3)
+    ws.fill_(0xAB)
+    heart.heart_mask_topp(np_gpu(qblk), np_gpu(kblk), np_gpu(tau), refresh=np_gpu(refresh), mask=m2,
+                          kept_idx=i2, kept_count=c2, workspace=ws)
+    torch.cuda.synchronize()
+    r = torch.from_numpy(refresh.astype(bool)).cuda()
+    assert torch.equal(m2[r], gm[r]) and torch.equal(c2[r], gc[r])
+    assert bool((m2[~r] == 7).all()) and bool((i2[~r] == -5).all()) and bool((c2[~r] == -3).all())
+
+
+@pytest.mark.parametrize("sliced", [False, True])
+def test_scores_large_logits_and_many_blocks(heart, sliced):
     # Nb = 600 (10 slots per lane), logits up to about +-30
     rng = np.random.default_rng(0)
     B, H, Nb, D = 1, 2, 600, 128
@@ -240,7 +292,7 @@ def test_scores_large_logits_and_many_blocks(heart):
     want = oracle.scores(qblk, kblk)
     out = torch.empty(want.shape, dtype=torch.float32, device="cuda")
     heart.heart_mask_topp(np_gpu(qblk), np_gpu(kblk), np_gpu(np.array([0.9, 0.5], np.float32)),
-                          scores_out=out)
+                          scores_out=out, workspace=_topp_workspace(heart, qblk.shape, sliced))
     torch.cuda.synchronize()
     assert_scores_close(out, want, "large logits")
 
