@@ -78,14 +78,19 @@ def test_mask_selection_random_cases(heart, seed):
                   min_keep=int(rng.choice([0, 1, 4, 500])))
         refresh = (rng.random((1, H)) < 0.8).astype(np.uint8)
         print(f"selection case {seed}/{case}: Nb={Nb} D={D} H={H} tau={tau.tolist()} {kw} "
-              f"refresh={refresh.tolist()}", flush=True)
+              f"refresh={refresh.tolist()} workspace={bool(case % 2)}", flush=True)
         sc = torch.zeros((1, H, Nb, Nb), device="cuda")
         gm = torch.zeros((1, H, Nb, Nb), dtype=torch.uint8, device="cuda")
         gi = torch.zeros((1, H, Nb, Nb), dtype=torch.int32, device="cuda")
         gc = torch.zeros((1, H, Nb), dtype=torch.int32, device="cuda")
+        # every second case with a workspace: the score stage on 8-bit slices for D = 64 / 128, and
+        # exactly the plain call for every other D
+        ws = None
+        if case % 2:
+            ws = torch.empty(heart.heart_mask_topp_workspace_bytes(1, H, Nb, D), dtype=torch.uint8, device="cuda")
         heart.heart_mask_topp(np_gpu(qb), np_gpu(kb), np_gpu(tau), refresh=np_gpu(refresh), scores_out=sc,
                               n_always_kv_blocks=kw["n_always_kv"], n_dense_q_blocks=kw["n_dense_q"],
-                              min_keep=kw["min_keep"], mask=gm, kept_idx=gi, kept_count=gc)
+                              min_keep=kw["min_keep"], mask=gm, kept_idx=gi, kept_count=gc, workspace=ws)
         torch.cuda.synchronize()
         s = sc.cpu().numpy()
         om, oi, oc = oracle.topp(s, tau, refresh=refresh, **kw)
